@@ -1,0 +1,181 @@
+"""CPU oracle for the R-KV decode-time KV-cache compression step.
+
+TEST INFRASTRUCTURE ONLY.  This is a plain, slow, float64 numpy implementation of what
+the paper's method computes for one KV head, written from the paper's equations so
+that a reader can check it against them by eye.  It shares no code with the HIP
+path and must never be imported by the product package: only the tests, the smoke
+check and the benchmark's CPU-baseline leg call it.  A matrix product, an argsort
+and exp are the only library primitives used as steps; nothing is blocked, fused or
+reordered.
+
+Notation follows the paper: N rows are held (budget + buffer), the last ``alpha``
+are the observation tokens (always kept), the first ``n = N - alpha`` are the
+candidates, and ``k = budget - alpha`` of them are selected (Sec. 3.1).
+
+Readings taken where the paper is silent or inconsistent (each is a default here):
+  * selection is per KV head (Sec. 3.4 speaks of a per-head budget and score Z^h_i);
+  * the softmax of the observation attention spans the n candidates only;
+  * grouped-query heads: max over the G raw scaled logit matrices, then softmax (Eq. 2-3);
+  * the 2W-wide max-pool is applied to every query row, then the rows are averaged
+    (Eq. 4); the window [i-W, i+W-1] is clipped to [0, n); W = 0 switches it off;
+  * "zero the similarities of the beta most recent similar tokens": for token i, among
+    the j with S[i][j] > T (strict), the beta largest j have S[i][j] set to 0 before
+    token i's own average is taken (Sec. 3.3 and the pseudo-code agree on this);
+  * the average divides by n (zeroed entries included);
+  * ties in the top-k are broken towards the larger (more recent) index;
+  * kept rows are emitted in ascending original order, followed by the observation rows.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Params:
+    alpha: int = 8           # observation window
+    budget: int = 0          # rows kept in total (selected + observation)
+    pool_w: int = 4          # W
+    beta: int = 1
+    sim_threshold: float = 0.5   # T
+    lam: float = 0.1         # lambda
+    eps: float = 1e-8
+
+
+# ----------------------------------------------------------------------------- decode
+def decode_bf16(bits: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns -> float64 (exact): sign, 8-bit exponent, 7-bit fraction."""
+    b = np.asarray(bits, dtype=np.uint16).astype(np.int64)
+    sign = np.where((b >> 15) & 1, -1.0, 1.0)
+    expo = (b >> 7) & 0xFF
+    frac = (b & 0x7F).astype(np.float64)
+    normal = sign * (1.0 + frac / 128.0) * np.exp2((expo - 127).astype(np.float64))
+    subnormal = sign * (frac / 128.0) * 2.0 ** -126
+    out = np.where(expo == 0, subnormal, normal)
+    special = np.where(frac == 0, sign * np.inf, np.nan)
+    return np.where(expo == 255, special, out)
+
+
+# ------------------------------------------------------------------------- importance
+def softmax_rows(x: np.ndarray) -> np.ndarray:
+    e = np.exp(x - x.max(axis=-1, keepdims=True))
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attention_weights(q: np.ndarray, k_cand: np.ndarray) -> np.ndarray:
+    """Eq. 1 (G = 1) and Eq. 2-3 (G > 1).
+
+    q [G, alpha, d] are the observation queries of the G query heads that share this
+    KV head, k_cand [n, d] the candidate keys.  Returns A [alpha, n], rows sum to 1.
+    """
+    G, alpha, d = q.shape
+    logits = np.stack([q[g] @ k_cand.T / np.sqrt(d) for g in range(G)])   # Eq. 2
+    pooled = logits.max(axis=0)                                           # max over the group
+    return softmax_rows(pooled)                                           # Eq. 3
+
+
+def stabilise(A: np.ndarray, W: int) -> np.ndarray:
+    """Eq. 4, first part: A~[j, i] = max(A[j, i-W .. i+W-1]), window clipped to the row."""
+    if W <= 0:
+        return A.copy()
+    alpha, n = A.shape
+    out = np.empty_like(A)
+    for i in range(n):
+        lo, hi = max(0, i - W), min(n - 1, i + W - 1)
+        out[:, i] = A[:, lo:hi + 1].max(axis=1)
+    return out
+
+
+def importance(q: np.ndarray, k_cand: np.ndarray, W: int) -> np.ndarray:
+    """Eq. 4: I[i] = mean over the alpha query rows of the stabilised attention."""
+    return stabilise(attention_weights(q, k_cand), W).mean(axis=0)
+
+
+# ------------------------------------------------------------------------- redundancy
+def cosine_similarity(k_cand: np.ndarray, eps: float) -> np.ndarray:
+    """Eq. 5: rows divided by (L2 norm + eps), Gram matrix, diagonal set to 0."""
+    norm = np.sqrt((k_cand * k_cand).sum(axis=1, keepdims=True))
+    kbar = k_cand / (norm + eps)
+    S = kbar @ kbar.T
+    np.fill_diagonal(S, 0.0)
+    return S
+
+
+def forgive_recent(S: np.ndarray, T: float, beta: int) -> np.ndarray:
+    """Sec. 3.3 "retention of recent tokens": for each token i take the indices j with
+    S[i, j] > T, and zero S[i, j] for the (up to) beta largest such j."""
+    S = S.copy()
+    n = S.shape[0]
+    hit = S > T
+    rev_cols = np.arange(n)[::-1]
+    for _ in range(max(0, int(beta))):
+        has = hit.any(axis=1)
+        if not has.any():
+            break
+        last = rev_cols[np.argmax(hit[:, ::-1], axis=1)]      # largest j with a hit, per row
+        rows = np.nonzero(has)[0]
+        S[rows, last[rows]] = 0.0
+        hit[rows, last[rows]] = False
+    return S
+
+
+def mean_similarity(k_cand: np.ndarray, T: float, beta: int, eps: float) -> np.ndarray:
+    """Eq. 6, first part: S-bar[i] = (1/n) sum_j S[i, j] after the zeroing above."""
+    S = forgive_recent(cosine_similarity(k_cand, eps), T, beta)
+    return S.sum(axis=1) / S.shape[0]
+
+
+def redundancy(k_cand: np.ndarray, T: float, beta: int, eps: float) -> np.ndarray:
+    """Eq. 6: R = softmax over the n candidates of S-bar."""
+    return softmax_rows(mean_similarity(k_cand, T, beta, eps)[None, :])[0]
+
+
+# -------------------------------------------------------------------- score and select
+def selection_score(I: np.ndarray, R: np.ndarray, lam: float) -> np.ndarray:
+    """Eq. 7: Z = lambda * I - (1 - lambda) * R."""
+    return lam * I - (1.0 - lam) * R
+
+
+def select_topk(Z: np.ndarray, k: int) -> np.ndarray:
+    """The k candidates with the largest Z (equal scores: larger index first), ascending."""
+    n = Z.shape[0]
+    order = sorted(range(n), key=lambda i: (-Z[i], -i))
+    return np.array(sorted(order[:k]), dtype=np.int64)
+
+
+# ----------------------------------------------------------------------- one KV head
+def compress_head(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, prm: Params):
+    """One KV head: q_bits [G, alpha, d], k_bits / v_bits [N, d] (bf16 bit patterns).
+
+    Returns a dict with importance, mean_sim, redundancy, score (each [n], float64),
+    kept (the budget kept row indices: k selected ascending, then n..N-1) and the
+    compacted k_out / v_out bit patterns [budget, d].
+    """
+    N = k_bits.shape[0]
+    n = N - prm.alpha
+    k_sel = prm.budget - prm.alpha
+    q = decode_bf16(q_bits)
+    k_cand = decode_bf16(k_bits[:n])
+    I = importance(q, k_cand, prm.pool_w)
+    sbar = mean_similarity(k_cand, float(np.float32(prm.sim_threshold)), prm.beta, prm.eps)
+    R = softmax_rows(sbar[None, :])[0]
+    Z = selection_score(I, R, float(np.float32(prm.lam)))
+    keep = select_topk(Z, k_sel)
+    kept = np.concatenate([keep, np.arange(n, N, dtype=np.int64)])
+    return dict(importance=I, mean_sim=sbar, redundancy=R, score=Z, kept=kept,
+                k_out=k_bits[kept].copy(), v_out=v_bits[kept].copy())
+
+
+def compress(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, prm: Params, heads=None):
+    """Batched form: q_bits [P, Hq, alpha, d], k_bits / v_bits [P, H, N, d].
+
+    Query head hq serves KV head hq // G (contiguous groups).  ``heads`` optionally
+    restricts the work to an iterable of (p, h) pairs; the result maps (p, h) to the
+    dict of ``compress_head``.
+    """
+    P, H = k_bits.shape[:2]
+    G = q_bits.shape[1] // H
+    todo = [(p, h) for p in range(P) for h in range(H)] if heads is None else list(heads)
+    return {(p, h): compress_head(q_bits[p, h * G:(h + 1) * G], k_bits[p, h], v_bits[p, h], prm)
+            for (p, h) in todo}
