@@ -1,0 +1,122 @@
+/*
+ * rkv.h — C ABI of the R-KV decode-time KV-cache compression step for AMD MI355X (gfx950).
+ *
+ * The step runs in every layer each time the decode buffer fills (Sec. 3.1): of the
+ * N = B_budget + B_buffer cached tokens the last `alpha` (observation tokens) are always
+ * kept, the first n = N - alpha are candidates, and k = budget - alpha candidates are
+ * selected per KV head by the joint score of Sec. 3.4.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library never
+ *     allocates, frees or keeps them.  `rkv_params` and `size_t*` are HOST pointers.
+ *   - bf16 tensors are row-major with the head dimension innermost and contiguous:
+ *       q_obs [P, q_heads, alpha, d]   observation queries; query head hq serves KV head
+ *                                      hq / G, G = q_heads / kv_heads (Sec. 3.2, GQA)
+ *       k, v  [P, kv_heads, N, d]      token order = row order; strides in `rkv_params`
+ *     fp32 / int32 outputs are dense: [P, kv_heads, n] or [P, kv_heads, budget].
+ *   - P = num_problems independent (sequence, layer) pairs are processed per call.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and the call returns without synchronising the device.
+ *   - `ws` is caller-provided device scratch of at least rkv_workspace_size() bytes,
+ *     256-byte aligned; contents need not be preserved between calls.
+ *   - Errors are returned as negative rkv_status values; when a negative status is returned
+ *     nothing has been enqueued and the outputs are untouched.
+ *   - Inputs holding NaN or Inf give unspecified scores (never out-of-bounds accesses).
+ *   - Supported shapes: d == 128, 1 <= alpha <= 64, G * alpha <= 64, N <= 65536,
+ *     token strides multiples of 8 elements (16-byte aligned rows).
+ */
+#ifndef RKV_H
+#define RKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RKV_OK = 0,
+  RKV_NOT_TRIGGERED = 1,     /* n <= budget - alpha... i.e. N <= budget: nothing to evict (Alg. 1 early returns) */
+  RKV_ERR_NULL = -1,         /* a required pointer is NULL */
+  RKV_ERR_SHAPE = -2,        /* inconsistent sizes: q_heads % kv_heads, budget <= alpha, N <= alpha, strides */
+  RKV_ERR_UNSUPPORTED = -3,  /* outside the supported shapes listed above, or unknown flag bits */
+  RKV_ERR_WORKSPACE = -4,    /* ws is NULL, misaligned or smaller than rkv_workspace_size() */
+  RKV_ERR_PARAM = -5,        /* lambda or sim_threshold outside [0, 1], beta < 0, eps < 0, pool_w < 0 */
+  RKV_ERR_HIP = -6           /* a kernel launch failed (hipGetLastError) */
+} rkv_status;
+
+typedef struct {
+  int32_t num_problems;      /* P >= 1 */
+  int32_t kv_heads;          /* H */
+  int32_t q_heads;           /* H * G */
+  int32_t n_tokens;          /* N = rows currently held per head (budget + buffer) */
+  int32_t head_dim;          /* d = 128 */
+  int32_t alpha;             /* observation window (paper: 8) */
+  int32_t budget;            /* rows kept per head = (budget - alpha) selected + alpha observation rows */
+  int32_t pool_w;            /* W of the 2W-wide max-pool window [i-W, i+W-1] (Eq. 4); 0 = no pooling */
+  int32_t beta;              /* most recent similar tokens whose similarity is zeroed (Sec. 3.3) */
+  float   sim_threshold;     /* T, strict '>' (Sec. 3.3) */
+  float   lambda;            /* trade-off of Eq. 7 (paper: 0.1) */
+  float   eps;               /* added to the key norm (Eq. 5, paper: 1e-8) */
+  uint32_t flags;            /* must be 0 */
+  int64_t k_stride_problem, k_stride_head, k_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
+  int64_t v_stride_problem, v_stride_head, v_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
+} rkv_params;
+
+/* Bytes of device scratch any entry point below needs for these params. */
+rkv_status rkv_workspace_size(const rkv_params* prm, size_t* bytes);
+
+/*
+ * Importance score, Sec. 3.2: scaled logits of the G query heads of each KV head against the
+ * n candidate keys (Eq. 2), element-wise max over the group, softmax over the candidates
+ * (Eq. 3; Eq. 1 when G = 1), 2W-wide sliding max per query row and mean over the alpha rows
+ * (Eq. 4).  Writes importance[P, H, n] (fp32).  `v` strides are ignored.
+ */
+rkv_status rkv_score_importance(const rkv_params* prm, const void* q_obs, const void* k,
+                                float* importance, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Redundancy score, Sec. 3.3: cosine similarity of the candidate keys with eps added to each
+ * norm and a zero diagonal (Eq. 5); for every token the similarities above T to its `beta`
+ * most recent (largest-index) similar tokens are zeroed; row average over n and softmax over
+ * the candidates (Eq. 6).  Writes redundancy[P, H, n]; if mean_sim is not NULL also the
+ * averages before the softmax, [P, H, n].  The n x n matrix is never stored.
+ */
+rkv_status rkv_score_redundancy(const rkv_params* prm, const void* k, float* redundancy,
+                                float* mean_sim, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Joint score and selection, Sec. 3.4 and 3.1: Z = lambda * I - (1 - lambda) * R (Eq. 7); per
+ * head the k = budget - alpha candidates with the largest Z are kept (equal Z: the larger index
+ * wins).  kept_idx[P, H, budget] (int32) receives the kept candidates in ascending order followed
+ * by the observation rows n .. N-1.  If score is not NULL it receives Z[P, H, n].
+ */
+rkv_status rkv_select_topk(const rkv_params* prm, const float* importance, const float* redundancy,
+                           float* score, int32_t* kept_idx, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Compaction (Alg. 1, gather + concatenate): k_out[p, h, r, :] = k[p, h, kept_idx[p, h, r], :],
+ * likewise v.  k_out, v_out are dense [P, H, budget, d] bf16 and must not overlap k, v.
+ * Every index must lie in [0, N); indices outside are clamped into that range.
+ */
+rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, const int32_t* kept_idx,
+                       void* k_out, void* v_out, void* stream);
+
+/*
+ * The whole step (Sec. 3.1-3.4, Alg. 1): the four calls above back to back on `stream`
+ * without host synchronisation.  kept_idx [P, H, budget] and score [P, H, n] are optional
+ * outputs (NULL to skip).  Returns RKV_NOT_TRIGGERED without enqueuing anything when
+ * N <= budget.
+ */
+rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
+                        void* k_out, void* v_out, int32_t* kept_idx, float* score,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* Static, NUL-terminated description of a status value. */
+const char* rkv_status_string(rkv_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RKV_H */

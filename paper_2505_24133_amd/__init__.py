@@ -1,0 +1,12 @@
+"""R-KV decode-time KV-cache compression step for AMD MI355X (gfx950).
+
+``rkv``    ctypes binding of the HIP library (loaded on first use; no CPU fallback)
+``synth``  seeded synthetic inputs with the shapes of the paper's workloads
+``build``  compiles csrc/*.hip into librkv.so with hipcc
+"""
+from . import synth  # noqa: F401
+from .rkv import (  # noqa: F401
+    RKV_NOT_TRIGGERED, RKV_OK, RkvError, RkvParams, Shape, load_library, make_workspace,
+    rkv_compact, rkv_compress, rkv_score_importance, rkv_score_redundancy, rkv_select_topk,
+    rkv_workspace_size, status_string,
+)

@@ -1,0 +1,169 @@
+// C ABI of librkv: argument validation, workspace carve-up and kernel sequencing.
+// Nothing here touches device memory from the host or synchronises the stream.
+#include <math.h>
+
+#include "rkv_internal.h"
+
+namespace rkv {
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+rkv_status make_plan(const rkv_params* prm, Plan* pl) {
+  if (prm == nullptr) return RKV_ERR_NULL;
+  const rkv_params& q = *prm;
+  if (q.num_problems < 1 || q.kv_heads < 1 || q.q_heads < 1 || q.alpha < 1 || q.n_tokens < 1 || q.budget < 1)
+    return RKV_ERR_SHAPE;
+  if (q.q_heads % q.kv_heads != 0) return RKV_ERR_SHAPE;
+  if (q.n_tokens <= q.alpha || q.budget <= q.alpha) return RKV_ERR_SHAPE;
+  if (q.head_dim != kHeadDim || q.flags != 0) return RKV_ERR_UNSUPPORTED;
+  const int G = q.q_heads / q.kv_heads;
+  if (q.alpha > kMaxQRows || (int64_t)G * q.alpha > kMaxQRows || q.n_tokens > 32768) return RKV_ERR_UNSUPPORTED;
+  if ((int64_t)q.num_problems * q.kv_heads > (1 << 22)) return RKV_ERR_UNSUPPORTED;
+  if (!(q.lambda >= 0.f && q.lambda <= 1.f) || !(q.sim_threshold >= 0.f && q.sim_threshold <= 1.f) ||
+      !(q.eps >= 0.f) || !isfinite(q.eps) || q.beta < 0 || q.pool_w < 0)
+    return RKV_ERR_PARAM;
+
+  pl->P = q.num_problems; pl->H = q.kv_heads; pl->G = G; pl->N = q.n_tokens; pl->alpha = q.alpha;
+  pl->n = q.n_tokens - q.alpha; pl->budget = q.budget; pl->k_sel = q.budget - q.alpha;
+  pl->W = q.pool_w; pl->beta = q.beta; pl->T = q.sim_threshold; pl->lambda = q.lambda; pl->eps = q.eps;
+  pl->heads = q.num_problems * q.kv_heads;
+  pl->chunks = (pl->n + kChunk - 1) / kChunk;
+  pl->n_pad = pl->chunks * kChunk;
+
+  auto strides = [&](int64_t sp, int64_t sh, int64_t st, int64_t* op, int64_t* oh, int64_t* ot) -> bool {
+    if (sp == 0 && sh == 0 && st == 0) {
+      *ot = kHeadDim; *oh = (int64_t)q.n_tokens * kHeadDim; *op = *oh * q.kv_heads;
+      return true;
+    }
+    if (st < kHeadDim || (st % 8) != 0 || (sh % 8) != 0 || (sp % 8) != 0 || sh < 0 || sp < 0) return false;
+    if (q.kv_heads > 1 && sh == 0) return false;
+    if (q.num_problems > 1 && sp == 0) return false;
+    *op = sp; *oh = sh; *ot = st;
+    return true;
+  };
+  if (!strides(q.k_stride_problem, q.k_stride_head, q.k_stride_token, &pl->ksp, &pl->ksh, &pl->kst)) return RKV_ERR_SHAPE;
+  if (!strides(q.v_stride_problem, q.v_stride_head, q.v_stride_token, &pl->vsp, &pl->vsh, &pl->vst)) return RKV_ERR_SHAPE;
+
+  size_t off = 0;
+  const size_t heads = (size_t)pl->heads, np = (size_t)pl->n_pad;
+  auto take = [&](size_t bytes) { const size_t o = off; off = align_up(off + bytes); return o; };
+  pl->off_rnorm = take(heads * np * 4);
+  pl->off_upart = take(heads * pl->chunks * kHeadDim * 4);
+  pl->off_logit = take(heads * pl->alpha * np * 4);
+  pl->off_stats = take(heads * pl->chunks * pl->alpha * 2 * 4);
+  pl->off_sbar = take(heads * np * 4);
+  pl->off_imp = take(heads * np * 4);
+  pl->off_red = take(heads * np * 4);
+  pl->off_keys = take(heads * np * 4);
+  pl->off_idx = take(heads * (size_t)pl->budget * 4);
+  pl->total = off;
+  return RKV_OK;
+}
+
+static rkv_status check_ws(const Plan& pl, const void* ws, size_t ws_bytes) {
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < pl.total) return RKV_ERR_WORKSPACE;
+  return RKV_OK;
+}
+
+static rkv_status hip_status(hipError_t e) { return e == hipSuccess ? RKV_OK : RKV_ERR_HIP; }
+
+}  // namespace rkv
+
+using namespace rkv;
+
+extern "C" {
+
+rkv_status rkv_workspace_size(const rkv_params* prm, size_t* bytes) {
+  if (bytes == nullptr) return RKV_ERR_NULL;
+  Plan pl;
+  const rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  *bytes = pl.total;
+  return RKV_OK;
+}
+
+rkv_status rkv_score_importance(const rkv_params* prm, const void* q_obs, const void* k,
+                                float* importance, void* ws, size_t ws_bytes, void* stream) {
+  if (q_obs == nullptr || k == nullptr || importance == nullptr) return RKV_ERR_NULL;
+  Plan pl;
+  rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* w = static_cast<char*>(ws);
+  if ((s = hip_status(launch_prepass(pl, q_obs, k, w, st))) != RKV_OK) return s;
+  return hip_status(launch_finalize(pl, kModeImportance, w, nullptr, nullptr, importance, nullptr, nullptr,
+                                    nullptr, nullptr, st));
+}
+
+rkv_status rkv_score_redundancy(const rkv_params* prm, const void* k, float* redundancy,
+                                float* mean_sim, void* ws, size_t ws_bytes, void* stream) {
+  if (k == nullptr || redundancy == nullptr) return RKV_ERR_NULL;
+  Plan pl;
+  rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* w = static_cast<char*>(ws);
+  if ((s = hip_status(launch_prepass(pl, nullptr, k, w, st))) != RKV_OK) return s;
+  if ((s = hip_status(launch_gram(pl, k, w, st))) != RKV_OK) return s;
+  return hip_status(launch_finalize(pl, kModeRedundancy, w, nullptr, nullptr, nullptr, redundancy, mean_sim,
+                                    nullptr, nullptr, st));
+}
+
+rkv_status rkv_select_topk(const rkv_params* prm, const float* importance, const float* redundancy,
+                           float* score, int32_t* kept_idx, void* ws, size_t ws_bytes, void* stream) {
+  if (importance == nullptr || redundancy == nullptr || kept_idx == nullptr) return RKV_ERR_NULL;
+  Plan pl;
+  rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
+  if (pl.N <= pl.budget) return RKV_NOT_TRIGGERED;
+  return hip_status(launch_finalize(pl, kModeSelect, static_cast<char*>(ws), importance, redundancy, nullptr,
+                                    nullptr, nullptr, score, kept_idx, static_cast<hipStream_t>(stream)));
+}
+
+rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, const int32_t* kept_idx,
+                       void* k_out, void* v_out, void* stream) {
+  if (k == nullptr || v == nullptr || kept_idx == nullptr || k_out == nullptr || v_out == nullptr) return RKV_ERR_NULL;
+  Plan pl;
+  const rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  return hip_status(launch_gather(pl, k, v, kept_idx, k_out, v_out, static_cast<hipStream_t>(stream)));
+}
+
+rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
+                        void* k_out, void* v_out, int32_t* kept_idx, float* score,
+                        void* ws, size_t ws_bytes, void* stream) {
+  if (q_obs == nullptr || k == nullptr || v == nullptr || k_out == nullptr || v_out == nullptr) return RKV_ERR_NULL;
+  Plan pl;
+  rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
+  if (pl.N <= pl.budget) return RKV_NOT_TRIGGERED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* w = static_cast<char*>(ws);
+  int32_t* idx = kept_idx ? kept_idx : reinterpret_cast<int32_t*>(w + pl.off_idx);
+  if ((s = hip_status(launch_prepass(pl, q_obs, k, w, st))) != RKV_OK) return s;
+  if ((s = hip_status(launch_gram(pl, k, w, st))) != RKV_OK) return s;
+  if ((s = hip_status(launch_finalize(pl, kModeImportance | kModeRedundancy | kModeSelect, w, nullptr, nullptr,
+                                      nullptr, nullptr, nullptr, score, idx, st))) != RKV_OK)
+    return s;
+  return hip_status(launch_gather(pl, k, v, idx, k_out, v_out, st));
+}
+
+const char* rkv_status_string(rkv_status s) {
+  switch (s) {
+    case RKV_OK: return "ok";
+    case RKV_NOT_TRIGGERED: return "not triggered: the cache does not exceed the budget";
+    case RKV_ERR_NULL: return "a required pointer is NULL";
+    case RKV_ERR_SHAPE: return "inconsistent shape or strides";
+    case RKV_ERR_UNSUPPORTED: return "shape outside the supported range";
+    case RKV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case RKV_ERR_PARAM: return "hyper-parameter out of range";
+    case RKV_ERR_HIP: return "HIP launch failure";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

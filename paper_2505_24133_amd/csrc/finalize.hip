@@ -1,0 +1,258 @@
+// Per-head finalisation, one workgroup per KV head:
+//   importance : complete the softmax over all candidates from the pre-pass's per-chunk
+//                statistics, 2W-wide sliding max per query row, mean over the alpha rows (Eq. 3-4)
+//   redundancy : softmax over the candidates of the mean similarities (Eq. 6)
+//   select     : Z = lambda I - (1 - lambda) R (Eq. 7), exact k-th largest by a 4 x 8-bit radix
+//                select on order-preserving integer keys held in LDS, ties resolved towards the
+//                larger index, kept indices emitted in ascending order by a workgroup prefix scan,
+//                followed by the alpha observation rows (Sec. 3.1).
+#include "rkv_internal.h"
+
+namespace rkv {
+
+namespace {
+
+constexpr int kFinThreads = 1024;
+constexpr int kFinWaves = kFinThreads / 64;
+
+struct FinArgs {
+  const float* logit;    // [heads][alpha][n_pad]
+  const float* stats;    // [heads][chunks][alpha][2]
+  const float* sbar;     // [heads][n_pad]
+  const float* imp_in;   // [heads][n] (select-only mode)
+  const float* red_in;   // [heads][n]
+  float* imp_out;        // [heads][n] or nullptr
+  float* red_out;        // [heads][n] or nullptr
+  float* sbar_out;       // [heads][n] or nullptr
+  float* score_out;      // [heads][n] or nullptr
+  int32_t* kept;         // [heads][budget]
+  int n, n_pad, chunks, alpha, W, k_sel, budget;
+  float lambda;
+};
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+// Workgroup reductions in a fixed order (deterministic); `buf` holds kFinWaves floats.
+__device__ float block_max(float v, float* buf) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = buf[0];
+  for (int w = 1; w < kFinWaves; ++w) r = fmaxf(r, buf[w]);
+  return r;
+}
+__device__ float block_sum(float v, float* buf) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = buf[0];
+  for (int w = 1; w < kFinWaves; ++w) r += buf[w];
+  return r;
+}
+// Exclusive prefix sum of one uint per thread over the workgroup; also returns the total.
+__device__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* buf, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t y = __shfl_up(inc, o);
+    if (lane >= o) inc += y;
+  }
+  __syncthreads();
+  if (lane == 63) buf[wave] = inc;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+  for (int w = 0; w < kFinWaves; ++w) {
+    const uint32_t x = buf[w];
+    if (w < wave) before += x;
+    all += x;
+  }
+  *total = all;
+  return before + inc - v;
+}
+
+__device__ __forceinline__ uint32_t order_key(float z) {
+  const uint32_t b = __float_as_uint(z);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
+  extern __shared__ uint32_t keys[];            // n_pad order-preserving keys (select mode)
+  __shared__ float red[kFinWaves];
+  __shared__ uint32_t scan_buf[kFinWaves];
+  __shared__ float gmax[kMaxQRows], ginv[kMaxQRows];
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sel[3];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int head = blockIdx.x;
+  const int n = a.n;
+  const float* lg = a.logit + (int64_t)head * a.alpha * a.n_pad;
+  const float* sb = a.sbar + (int64_t)head * a.n_pad;
+
+  // ---- softmax denominators
+  if constexpr ((MODE & kModeImportance) != 0) {
+    if (t < a.alpha) {
+      const float* st = a.stats + ((int64_t)head * a.chunks * a.alpha + t) * 2;
+      float m = -INFINITY;
+      for (int c = 0; c < a.chunks; ++c) m = fmaxf(m, st[(int64_t)c * a.alpha * 2]);
+      float den = 0.f;
+      for (int c = 0; c < a.chunks; ++c)
+        den += st[(int64_t)c * a.alpha * 2 + 1] * expf(st[(int64_t)c * a.alpha * 2] - m);
+      gmax[t] = m;
+      ginv[t] = 1.0f / (den * (float)a.alpha);
+    }
+  }
+  float smax = 0.f, sinv = 0.f;
+  if constexpr ((MODE & kModeRedundancy) != 0) {
+    float m = -INFINITY;
+    for (int i = t; i < n; i += kFinThreads) m = fmaxf(m, sb[i]);
+    smax = block_max(m, red);
+    float s = 0.f;
+    for (int i = t; i < n; i += kFinThreads) s += expf(sb[i] - smax);
+    sinv = 1.0f / block_sum(s, red);
+  }
+  __syncthreads();
+
+  // ---- per-candidate scores
+  for (int i = t; i < n; i += kFinThreads) {
+    float imp = 0.f, rd = 0.f;
+    if constexpr ((MODE & kModeImportance) != 0) {
+      const int lo = (a.W > 0) ? max(0, i - a.W) : i;
+      const int hi = (a.W > 0) ? min(n - 1, i + a.W - 1) : i;
+      for (int j = 0; j < a.alpha; ++j) {
+        const float* row = lg + (int64_t)j * a.n_pad;
+        float m = row[lo];
+        for (int c = lo + 1; c <= hi; ++c) m = fmaxf(m, row[c]);
+        imp += expf(m - gmax[j]) * ginv[j];
+      }
+      if (a.imp_out) a.imp_out[(int64_t)head * n + i] = imp;
+    } else if constexpr ((MODE & kModeSelect) != 0) {
+      imp = a.imp_in[(int64_t)head * n + i];
+    }
+    if constexpr ((MODE & kModeRedundancy) != 0) {
+      const float s = sb[i];
+      rd = expf(s - smax) * sinv;
+      if (a.red_out) a.red_out[(int64_t)head * n + i] = rd;
+      if (a.sbar_out) a.sbar_out[(int64_t)head * n + i] = s;
+    } else if constexpr ((MODE & kModeSelect) != 0) {
+      rd = a.red_in[(int64_t)head * n + i];
+    }
+    if constexpr ((MODE & kModeSelect) != 0) {
+      const float z = a.lambda * imp - (1.0f - a.lambda) * rd;
+      if (a.score_out) a.score_out[(int64_t)head * n + i] = z;
+      keys[i] = order_key(z);
+    }
+  }
+
+  if constexpr ((MODE & kModeSelect) != 0) {
+    // ---- radix select: key of the k-th largest score
+    uint32_t prefix = 0, known = 0, krem = (uint32_t)a.k_sel, n_equal = 0;
+#pragma unroll 1
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      if (t < 256) hist[t] = 0;
+      __syncthreads();
+      for (int i0 = 0; i0 < n; i0 += kFinThreads) {
+        const int i = i0 + t;
+        const uint32_t key = (i < n) ? keys[i] : 0u;
+        bool live = (i < n) && ((key & known) == prefix);
+        const uint32_t digit = (key >> shift) & 255u;
+        // scores of one head are often close: count the wave's most common digit with one atomic
+        const unsigned long long am = __ballot(live);
+        if (am != 0ull) {
+          const int first = __ffsll((long long)am) - 1;
+          const uint32_t d0 = __shfl(digit, first);
+          const unsigned long long same = __ballot(live && digit == d0);
+          if (lane == first) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+          live = live && (digit != d0);
+          if (live) atomicAdd(&hist[digit], 1u);
+        }
+      }
+      __syncthreads();
+      // the bin holding the krem-th largest: bins above it hold fewer than krem keys
+      uint32_t above = 0, total = 0;
+      const uint32_t mine = (t < 256) ? hist[255 - t] : 0u;      // thread t <-> bin 255 - t
+      above = block_exclusive_scan(mine, scan_buf, &total);
+      if (t < 256 && above < krem && above + mine >= krem) {
+        sel[0] = 255u - (uint32_t)t;
+        sel[1] = above;
+        sel[2] = mine;
+      }
+      __syncthreads();
+      prefix |= sel[0] << shift;
+      known |= 255u << shift;
+      krem -= sel[1];
+      n_equal = sel[2];
+      __syncthreads();
+    }
+    // keys > prefix are all kept; of the n_equal keys == prefix the krem with the largest indices
+    const uint32_t skip_eq = n_equal - krem;
+    int32_t* out = a.kept + (int64_t)head * a.budget;
+    uint32_t run_gt = 0, run_eq = 0;
+    for (int i0 = 0; i0 < n; i0 += kFinThreads) {
+      const int i = i0 + t;
+      const uint32_t key = (i < n) ? keys[i] : 0u;
+      const uint32_t gt = (i < n && key > prefix) ? 1u : 0u;
+      const uint32_t eq = (i < n && key == prefix) ? 1u : 0u;
+      uint32_t total;
+      const uint32_t ex = block_exclusive_scan(gt | (eq << 16), scan_buf, &total);
+      const uint32_t gt_before = run_gt + (ex & 0xffffu);
+      const uint32_t eq_before = run_eq + (ex >> 16);
+      const bool keep = gt || (eq && eq_before >= skip_eq);
+      if (keep) {
+        const uint32_t pos = gt_before + (eq_before > skip_eq ? eq_before - skip_eq : 0u);
+        out[pos] = i;
+      }
+      run_gt += total & 0xffffu;
+      run_eq += total >> 16;
+    }
+    for (int r = t; r < a.alpha; r += kFinThreads) out[a.k_sel + r] = n + r;
+  }
+}
+
+template <int MODE>
+hipError_t launch_mode(const FinArgs& a, int heads, size_t lds, hipStream_t stream) {
+  hipLaunchKernelGGL((finalize_kernel<MODE>), dim3(heads), dim3(kFinThreads), lds, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
+                           const float* imp_in, const float* red_in,
+                           float* imp_out, float* red_out, float* sbar_out,
+                           float* score_out, int32_t* kept_idx, hipStream_t stream) {
+  FinArgs a;
+  a.logit = reinterpret_cast<const float*>(ws + pl.off_logit);
+  a.stats = reinterpret_cast<const float*>(ws + pl.off_stats);
+  a.sbar = reinterpret_cast<const float*>(ws + pl.off_sbar);
+  a.imp_in = imp_in; a.red_in = red_in;
+  a.imp_out = imp_out; a.red_out = red_out; a.sbar_out = sbar_out; a.score_out = score_out;
+  a.kept = kept_idx;
+  a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks; a.alpha = pl.alpha; a.W = pl.W;
+  a.k_sel = pl.k_sel; a.budget = pl.budget;
+  a.lambda = pl.lambda;
+  const size_t lds = (mode & kModeSelect) ? (size_t)pl.n_pad * sizeof(uint32_t) : 0;
+  switch (mode) {
+    case kModeImportance: return launch_mode<kModeImportance>(a, pl.heads, lds, stream);
+    case kModeRedundancy: return launch_mode<kModeRedundancy>(a, pl.heads, lds, stream);
+    case kModeSelect: return launch_mode<kModeSelect>(a, pl.heads, lds, stream);
+    case kModeImportance | kModeRedundancy | kModeSelect:
+      return launch_mode<kModeImportance | kModeRedundancy | kModeSelect>(a, pl.heads, lds, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace rkv

@@ -1,0 +1,187 @@
+// Key pre-pass: one read of the candidate keys produces, per chunk of 128 keys,
+//   - the inverse norms r_i = 1 / (|K_i|_2 + eps)                      (Eq. 5)
+//   - the chunk's share of u = sum_i r_i K_i (used for closed-form row sums of the
+//     cosine matrix: sum_j S_ij = r_i K_i . u - S_ii)
+//   - the group-max scaled logits of the G*alpha observation query rows (Eq. 2-3, bf16 MFMA,
+//     fp32 accumulation) and the chunk's (max, sum exp) per query row for the softmax over
+//     all candidates, which the finalize kernel completes.
+// HBM-bound: every key byte is read exactly once, coalesced, and staged in LDS.
+#include "rkv_internal.h"
+
+namespace rkv {
+
+namespace {
+
+constexpr int kPrepassThreads = 256;
+constexpr int kLogitStride = kChunk + 8;   // floats; +8 puts the two half-waves on disjoint banks
+
+struct PrepassArgs {
+  const uint16_t* q;      // [P, Hq, alpha, d] or nullptr
+  const uint16_t* k;
+  float* rnorm;
+  float* upart;
+  float* logit;
+  float* stats;
+  int H, G, alpha, n, n_pad, chunks;
+  int64_t ksp, ksh, kst;
+  float eps, scale;
+};
+
+template <bool HAS_Q, int MT>
+__global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a) {
+  __shared__ __attribute__((aligned(16))) unsigned char ks[kChunk * kLdsRowBytes];
+  __shared__ float ured[4][kHeadDim];
+  __shared__ float lg[HAS_Q ? MT * 32 : 1][kLogitStride];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = t >> 6;
+  const int head = blockIdx.x / a.chunks;
+  const int chunk = blockIdx.x - head * a.chunks;
+  const int p = head / a.H;
+  const int h = head - p * a.H;
+  const int j0 = chunk * kChunk;
+  const uint16_t* kbase = a.k + p * a.ksp + h * a.ksh;
+
+  // ---- stage the chunk in LDS (coalesced 16-byte loads), norms and the chunk's share of u
+  const int c16 = t & 15;
+  const int rbase = t >> 4;
+  float uacc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) uacc[e] = 0.f;
+  uint4 regs[8];
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    const int grow = j0 + m * 16 + rbase;
+    regs[m] = make_uint4(0, 0, 0, 0);
+    if (grow < a.n) regs[m] = *reinterpret_cast<const uint4*>(kbase + (int64_t)grow * a.kst + c16 * 8);
+  }
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    const int row = m * 16 + rbase;
+    const int grow = j0 + row;
+    const uint4 x = regs[m];
+    *reinterpret_cast<uint4*>(ks + row * kLdsRowBytes + c16 * 16) = x;
+    const uint32_t w4[4] = {x.x, x.y, x.z, x.w};
+    float f[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      f[2 * e] = __uint_as_float(w4[e] << 16);
+      f[2 * e + 1] = __uint_as_float(w4[e] & 0xffff0000u);
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss = fmaf(f[e], f[e], ss);
+    ss += __shfl_xor(ss, 1);
+    ss += __shfl_xor(ss, 2);
+    ss += __shfl_xor(ss, 4);
+    ss += __shfl_xor(ss, 8);
+    const float r = (grow < a.n) ? 1.0f / (sqrtf(ss) + a.eps) : 0.f;
+    if (c16 == 0) a.rnorm[(int64_t)head * a.n_pad + grow] = r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) uacc[e] = fmaf(r, f[e], uacc[e]);
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    uacc[e] += __shfl_xor(uacc[e], 16);
+    uacc[e] += __shfl_xor(uacc[e], 32);
+  }
+  if (lane < 16) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ured[wave][lane * 8 + e] = uacc[e];
+  }
+  __syncthreads();
+  if (t < kHeadDim) {
+    const float s = (ured[0][t] + ured[1][t]) + (ured[2][t] + ured[3][t]);
+    a.upart[((int64_t)head * a.chunks + chunk) * kHeadDim + t] = s;
+  }
+
+  if constexpr (HAS_Q) {
+    // ---- logits: A = the G*alpha query rows of this KV head, B = 32 keys per wave
+    const int GA = a.G * a.alpha;
+    const uint16_t* qbase = a.q + ((int64_t)p * a.H * a.G + (int64_t)h * a.G) * a.alpha * kHeadDim;
+    f32x16 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
+    const int lrow = lane & 31;
+    const int khalf = lane >> 5;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + (wave * 32 + lrow) * kLdsRowBytes + kk * 32 + khalf * 16);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int qrow = mt * 32 + lrow;
+        uint4 qv = make_uint4(0, 0, 0, 0);
+        if (qrow < GA) qv = *reinterpret_cast<const uint4*>(qbase + qrow * kHeadDim + kk * 16 + khalf * 8);
+        bf16x8 qf;
+        __builtin_memcpy(&qf, &qv, 16);
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf, acc[mt], 0, 0, 0);
+      }
+    }
+    // accumulator layout: column (key) = lane % 32, row (query) = 8*(i/4) + 4*(lane/32) + i%4
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int qrow = mt * 32 + 8 * (i >> 2) + 4 * khalf + (i & 3);
+        lg[qrow][wave * 32 + lrow] = acc[mt][i] * a.scale;
+      }
+    __syncthreads();
+    // ---- max over the G query heads of the group, per (query position j, key)
+    {
+      const int key = t & (kChunk - 1);
+      const bool valid = (j0 + key) < a.n;
+      for (int j = t >> 7; j < a.alpha; j += kPrepassThreads / kChunk) {
+        float m = lg[j][key];
+        for (int g = 1; g < a.G; ++g) m = fmaxf(m, lg[g * a.alpha + j][key]);
+        if (valid) a.logit[((int64_t)head * a.alpha + j) * a.n_pad + j0 + key] = m;
+        lg[j][key] = valid ? m : -INFINITY;      // row j (g = 0) is read by this thread only
+      }
+    }
+    __syncthreads();
+    // ---- per-chunk softmax statistics for each query position
+    for (int j = wave; j < a.alpha; j += 4) {
+      const float x0 = lg[j][lane], x1 = lg[j][lane + 64];
+      float m = fmaxf(x0, x1);
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+      float s = expf(x0 - m) + expf(x1 - m);     // exp(-inf) = 0 for masked keys; key j0 is always valid
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+      if (lane == 0) {
+        float* st = a.stats + (((int64_t)head * a.chunks + chunk) * a.alpha + j) * 2;
+        st[0] = m;
+        st[1] = s;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char* ws, hipStream_t stream) {
+  PrepassArgs a;
+  a.q = static_cast<const uint16_t*>(q_obs);
+  a.k = static_cast<const uint16_t*>(k);
+  a.rnorm = reinterpret_cast<float*>(ws + pl.off_rnorm);
+  a.upart = reinterpret_cast<float*>(ws + pl.off_upart);
+  a.logit = reinterpret_cast<float*>(ws + pl.off_logit);
+  a.stats = reinterpret_cast<float*>(ws + pl.off_stats);
+  a.H = pl.H; a.G = pl.G; a.alpha = pl.alpha; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks;
+  a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
+  a.eps = pl.eps;
+  a.scale = 1.0f / sqrtf((float)kHeadDim);
+  const dim3 grid((unsigned)((int64_t)pl.heads * pl.chunks)), block(kPrepassThreads);
+  if (q_obs == nullptr) {
+    hipLaunchKernelGGL((prepass_kernel<false, 1>), grid, block, 0, stream, a);
+  } else if (pl.G * pl.alpha <= 32) {
+    hipLaunchKernelGGL((prepass_kernel<true, 1>), grid, block, 0, stream, a);
+  } else {
+    hipLaunchKernelGGL((prepass_kernel<true, 2>), grid, block, 0, stream, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace rkv

@@ -1,0 +1,62 @@
+// Internal declarations shared by the HIP translation units of librkv (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "rkv.h"
+
+namespace rkv {
+
+constexpr int kHeadDim = 128;        // d
+constexpr int kChunk = 128;          // keys per workgroup in the key pre-pass
+constexpr int kMaxQRows = 64;        // G * alpha rows of observation queries per KV head
+constexpr int kRowBytes = kHeadDim * 2;
+constexpr int kLdsRowBytes = kRowBytes + 16;   // padded LDS row: 16-byte fragments of 8 consecutive rows hit distinct banks
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+// Derived sizes and the workspace carve-up (all offsets in bytes, 256-byte aligned).
+struct Plan {
+  int P, H, G, N, n, k_sel, alpha, budget, W, beta;
+  int heads;          // P * H
+  int chunks;         // ceil(n / kChunk)
+  int n_pad;          // chunks * kChunk
+  float T, lambda, eps;
+  int64_t ksp, ksh, kst;   // key strides (elements)
+  int64_t vsp, vsh, vst;   // value strides (elements)
+  size_t off_rnorm;   // float [heads][n_pad]           1 / (|K_i| + eps), 0 for i >= n
+  size_t off_upart;   // float [heads][chunks][128]     per-chunk sums of r_i K_i
+  size_t off_logit;   // float [heads][alpha][n_pad]    group-max scaled logits
+  size_t off_stats;   // float [heads][chunks][alpha][2] per-chunk (max, sum exp)
+  size_t off_sbar;    // float [heads][n_pad]           mean similarity
+  size_t off_imp;     // float [heads][n_pad]           importance (fused path)
+  size_t off_red;     // float [heads][n_pad]           redundancy (fused path)
+  size_t off_keys;    // uint  [heads][n_pad]           order-preserving keys of Z
+  size_t off_idx;     // int   [heads][budget]          kept indices when the caller passes none
+  size_t total;
+};
+
+rkv_status make_plan(const rkv_params* prm, Plan* plan);
+
+// Kernel launchers (each enqueues on `stream` and returns hipGetLastError()).
+hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char* ws, hipStream_t stream);
+hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stream);
+
+enum SelectMode : int {
+  kModeImportance = 1,   // workspace logits -> importance
+  kModeRedundancy = 2,   // workspace mean similarity -> redundancy
+  kModeSelect = 4,       // importance, redundancy -> Z, kept indices
+};
+hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
+                           const float* imp_in, const float* red_in,
+                           float* imp_out, float* red_out, float* sbar_out,
+                           float* score_out, int32_t* kept_idx, hipStream_t stream);
+hipError_t launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* kept_idx,
+                         void* k_out, void* v_out, hipStream_t stream);
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+}  // namespace rkv

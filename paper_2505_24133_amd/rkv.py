@@ -1,0 +1,251 @@
+"""ctypes binding of librkv.so: the same entry points as ``include/rkv.h``, taking torch
+tensors that live on the GPU.  This layer only marshals arguments (pointers, sizes, the
+current HIP stream) and allocates outputs / scratch with torch; every step of the
+compression runs in the library's HIP kernels.  There is no CPU fallback: if the
+library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librkv.so")
+
+RKV_OK = 0
+RKV_NOT_TRIGGERED = 1
+RKV_ERR_NULL = -1
+RKV_ERR_SHAPE = -2
+RKV_ERR_UNSUPPORTED = -3
+RKV_ERR_WORKSPACE = -4
+RKV_ERR_PARAM = -5
+RKV_ERR_HIP = -6
+
+
+class RkvParams(ctypes.Structure):
+    """Mirror of ``rkv_params``."""
+    _fields_ = [
+        ("num_problems", ctypes.c_int32), ("kv_heads", ctypes.c_int32), ("q_heads", ctypes.c_int32),
+        ("n_tokens", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("alpha", ctypes.c_int32),
+        ("budget", ctypes.c_int32), ("pool_w", ctypes.c_int32), ("beta", ctypes.c_int32),
+        ("sim_threshold", ctypes.c_float), ("lam", ctypes.c_float), ("eps", ctypes.c_float),
+        ("flags", ctypes.c_uint32),
+        ("k_stride_problem", ctypes.c_int64), ("k_stride_head", ctypes.c_int64), ("k_stride_token", ctypes.c_int64),
+        ("v_stride_problem", ctypes.c_int64), ("v_stride_head", ctypes.c_int64), ("v_stride_token", ctypes.c_int64),
+    ]
+
+
+class RkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load librkv.so (built in-tree by ``paper_2505_24133_amd.build``); raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2505_24133_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    P, V, S = ctypes.POINTER(RkvParams), ctypes.c_void_p, ctypes.c_size_t
+    lib.rkv_workspace_size.argtypes = [P, ctypes.POINTER(S)]
+    lib.rkv_score_importance.argtypes = [P, V, V, V, V, S, V]
+    lib.rkv_score_redundancy.argtypes = [P, V, V, V, V, S, V]
+    lib.rkv_select_topk.argtypes = [P, V, V, V, V, V, S, V]
+    lib.rkv_compact.argtypes = [P, V, V, V, V, V, V]
+    lib.rkv_compress.argtypes = [P, V, V, V, V, V, V, V, V, S, V]
+    for name in ("rkv_workspace_size", "rkv_score_importance", "rkv_score_redundancy", "rkv_select_topk",
+                 "rkv_compact", "rkv_compress"):
+        getattr(lib, name).restype = ctypes.c_int
+    lib.rkv_status_string.argtypes = [ctypes.c_int]
+    lib.rkv_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().rkv_status_string(int(status)).decode()
+
+
+@dataclass
+class Shape:
+    num_problems: int
+    kv_heads: int
+    q_heads: int
+    n_tokens: int
+    budget: int
+    alpha: int = 8
+    head_dim: int = 128
+    pool_w: int = 4
+    beta: int = 1
+    sim_threshold: float = 0.5
+    lam: float = 0.1
+    eps: float = 1e-8
+
+    def params(self, k: Optional[torch.Tensor] = None, v: Optional[torch.Tensor] = None) -> RkvParams:
+        p = RkvParams(self.num_problems, self.kv_heads, self.q_heads, self.n_tokens, self.head_dim, self.alpha,
+                      self.budget, self.pool_w, self.beta, self.sim_threshold, self.lam, self.eps, 0,
+                      0, 0, 0, 0, 0, 0)
+        if k is not None:
+            p.k_stride_problem, p.k_stride_head, p.k_stride_token = k.stride(0), k.stride(1), k.stride(2)
+        if v is not None:
+            p.v_stride_problem, p.v_stride_head, p.v_stride_token = v.stride(0), v.stride(1), v.stride(2)
+        return p
+
+    @property
+    def n_cand(self) -> int:
+        return self.n_tokens - self.alpha
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _need_gpu(*tensors: torch.Tensor) -> None:
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise RuntimeError("librkv works on GPU tensors only; there is no CPU path")
+
+
+def _check_kv(shape: Shape, t: torch.Tensor, what: str) -> None:
+    want = (shape.num_problems, shape.kv_heads, shape.n_tokens, shape.head_dim)
+    if tuple(t.shape) != want or t.dtype != torch.bfloat16 or t.stride(3) != 1:
+        raise ValueError(f"{what} must be bf16 {want} with a contiguous last dimension, got {tuple(t.shape)} {t.dtype}")
+
+
+def _check_q(shape: Shape, q: torch.Tensor) -> None:
+    want = (shape.num_problems, shape.q_heads, shape.alpha, shape.head_dim)
+    if tuple(q.shape) != want or q.dtype != torch.bfloat16 or not q.is_contiguous():
+        raise ValueError(f"q_obs must be contiguous bf16 {want}")
+
+
+def rkv_workspace_size(shape: Shape) -> int:
+    n = ctypes.c_size_t(0)
+    prm = shape.params()
+    s = load_library().rkv_workspace_size(ctypes.byref(prm), ctypes.byref(n))
+    if s != RKV_OK:
+        raise RkvError(s, "rkv_workspace_size")
+    return int(n.value)
+
+
+def make_workspace(shape: Shape, device="cuda") -> torch.Tensor:
+    return torch.empty(rkv_workspace_size(shape) + 256, dtype=torch.uint8, device=device)
+
+
+def _ws_args(shape: Shape, ws: Optional[torch.Tensor], device) -> Tuple[torch.Tensor, int, int]:
+    if ws is None:
+        ws = make_workspace(shape, device)
+    base = ws.data_ptr()
+    aligned = (base + 255) & ~255
+    return ws, aligned, ws.numel() - (aligned - base)
+
+
+def rkv_score_importance(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, ws: Optional[torch.Tensor] = None,
+                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _need_gpu(q_obs, k)
+    _check_q(shape, q_obs)
+    _check_kv(shape, k, "k")
+    if out is None:
+        out = torch.empty((shape.num_problems, shape.kv_heads, shape.n_cand), dtype=torch.float32, device=k.device)
+    ws, wp, wb = _ws_args(shape, ws, k.device)
+    prm = shape.params(k)
+    s = load_library().rkv_score_importance(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(out), wp, wb, _stream())
+    if s != RKV_OK:
+        raise RkvError(s, "rkv_score_importance")
+    return out
+
+
+def rkv_score_redundancy(shape: Shape, k: torch.Tensor, ws: Optional[torch.Tensor] = None,
+                         want_mean_sim: bool = False):
+    _need_gpu(k)
+    _check_kv(shape, k, "k")
+    red = torch.empty((shape.num_problems, shape.kv_heads, shape.n_cand), dtype=torch.float32, device=k.device)
+    ms = torch.empty_like(red) if want_mean_sim else None
+    ws, wp, wb = _ws_args(shape, ws, k.device)
+    prm = shape.params(k)
+    s = load_library().rkv_score_redundancy(ctypes.byref(prm), _ptr(k), _ptr(red), _ptr(ms), wp, wb, _stream())
+    if s != RKV_OK:
+        raise RkvError(s, "rkv_score_redundancy")
+    return (red, ms) if want_mean_sim else red
+
+
+def rkv_select_topk(shape: Shape, importance: torch.Tensor, redundancy: torch.Tensor,
+                    ws: Optional[torch.Tensor] = None, want_score: bool = False):
+    _need_gpu(importance, redundancy)
+    want = (shape.num_problems, shape.kv_heads, shape.n_cand)
+    for t in (importance, redundancy):
+        if tuple(t.shape) != want or t.dtype != torch.float32 or not t.is_contiguous():
+            raise ValueError(f"scores must be contiguous fp32 {want}")
+    dev = importance.device
+    kept = torch.empty((shape.num_problems, shape.kv_heads, shape.budget), dtype=torch.int32, device=dev)
+    score = torch.empty(want, dtype=torch.float32, device=dev) if want_score else None
+    ws, wp, wb = _ws_args(shape, ws, dev)
+    prm = shape.params()
+    s = load_library().rkv_select_topk(ctypes.byref(prm), _ptr(importance), _ptr(redundancy), _ptr(score),
+                                       _ptr(kept), wp, wb, _stream())
+    if s != RKV_OK:
+        raise RkvError(s, "rkv_select_topk")
+    return (kept, score) if want_score else kept
+
+
+def rkv_compact(shape: Shape, k: torch.Tensor, v: torch.Tensor, kept_idx: torch.Tensor,
+                k_out: Optional[torch.Tensor] = None, v_out: Optional[torch.Tensor] = None):
+    _need_gpu(k, v, kept_idx)
+    _check_kv(shape, k, "k")
+    _check_kv(shape, v, "v")
+    want = (shape.num_problems, shape.kv_heads, shape.budget)
+    if tuple(kept_idx.shape) != want or kept_idx.dtype != torch.int32 or not kept_idx.is_contiguous():
+        raise ValueError(f"kept_idx must be contiguous int32 {want}")
+    oshape = (shape.num_problems, shape.kv_heads, shape.budget, shape.head_dim)
+    if k_out is None:
+        k_out = torch.empty(oshape, dtype=torch.bfloat16, device=k.device)
+    if v_out is None:
+        v_out = torch.empty(oshape, dtype=torch.bfloat16, device=k.device)
+    prm = shape.params(k, v)
+    s = load_library().rkv_compact(ctypes.byref(prm), _ptr(k), _ptr(v), _ptr(kept_idx), _ptr(k_out), _ptr(v_out),
+                                   _stream())
+    if s != RKV_OK:
+        raise RkvError(s, "rkv_compact")
+    return k_out, v_out
+
+
+def rkv_compress(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                 ws: Optional[torch.Tensor] = None, k_out: Optional[torch.Tensor] = None,
+                 v_out: Optional[torch.Tensor] = None, kept_idx: Optional[torch.Tensor] = None,
+                 score: Optional[torch.Tensor] = None, want_idx: bool = True, want_score: bool = False):
+    """The whole step.  Returns (status, k_out, v_out, kept_idx, score); status is RKV_OK or
+    RKV_NOT_TRIGGERED (then nothing was computed)."""
+    _need_gpu(q_obs, k, v)
+    _check_q(shape, q_obs)
+    _check_kv(shape, k, "k")
+    _check_kv(shape, v, "v")
+    dev = k.device
+    oshape = (shape.num_problems, shape.kv_heads, shape.budget, shape.head_dim)
+    if k_out is None:
+        k_out = torch.empty(oshape, dtype=torch.bfloat16, device=dev)
+    if v_out is None:
+        v_out = torch.empty(oshape, dtype=torch.bfloat16, device=dev)
+    if kept_idx is None and want_idx:
+        kept_idx = torch.empty(oshape[:3], dtype=torch.int32, device=dev)
+    if score is None and want_score:
+        score = torch.empty((shape.num_problems, shape.kv_heads, shape.n_cand), dtype=torch.float32, device=dev)
+    ws, wp, wb = _ws_args(shape, ws, dev)
+    prm = shape.params(k, v)
+    s = load_library().rkv_compress(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out),
+                                    _ptr(kept_idx), _ptr(score), wp, wb, _stream())
+    if s < 0:
+        raise RkvError(s, "rkv_compress")
+    return s, k_out, v_out, kept_idx, score

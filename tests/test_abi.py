@@ -1,0 +1,101 @@
+"""The C-ABI library loads, exports every symbol declared in include/rkv.h, and its host-side
+validation returns the documented status codes without touching a GPU.  CPU only."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_24133_amd import rkv
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(rkv.LIB_PATH):
+        from paper_2505_24133_amd.build import build
+        build()
+    return rkv.load_library()
+
+
+def declared_symbols(repo_root):
+    text = open(os.path.join(repo_root, "include", "rkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rkv_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib, repo_root):
+    names = declared_symbols(repo_root)
+    assert names == ["rkv_compact", "rkv_compress", "rkv_score_importance", "rkv_score_redundancy",
+                     "rkv_select_topk", "rkv_status_string", "rkv_workspace_size"]
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(rkv.__dict__) >= set(names) - {"rkv_status_string"}
+
+
+def test_params_struct_layout_matches_header():
+    assert ctypes.sizeof(rkv.RkvParams) == 13 * 4 + 4 + 6 * 8      # 13 32-bit fields, pad to 8, 6 strides
+    assert rkv.RkvParams.k_stride_problem.offset == 56
+
+
+def shape(**kw):
+    base = dict(num_problems=2, kv_heads=8, q_heads=32, n_tokens=1152, budget=1024)
+    base.update(kw)
+    return rkv.Shape(**base)
+
+
+def ws_status(lib, s):
+    n = ctypes.c_size_t(0)
+    p = s.params()
+    return lib.rkv_workspace_size(ctypes.byref(p), ctypes.byref(n)), n.value
+
+
+def test_workspace_size_and_validation(lib):
+    st, nbytes = ws_status(lib, shape())
+    assert st == rkv.RKV_OK and nbytes > 0 and nbytes % 256 == 0
+    st2, nbytes2 = ws_status(lib, shape(num_problems=4))
+    assert st2 == rkv.RKV_OK and nbytes2 > nbytes
+    assert ws_status(lib, shape(q_heads=30))[0] == rkv.RKV_ERR_SHAPE
+    assert ws_status(lib, shape(budget=8))[0] == rkv.RKV_ERR_SHAPE
+    assert ws_status(lib, shape(n_tokens=8))[0] == rkv.RKV_ERR_SHAPE
+    assert ws_status(lib, shape(head_dim=64))[0] == rkv.RKV_ERR_UNSUPPORTED
+    assert ws_status(lib, shape(q_heads=8 * 9))[0] == rkv.RKV_ERR_UNSUPPORTED     # G * alpha = 72 > 64
+    assert ws_status(lib, shape(n_tokens=40000, budget=30000))[0] == rkv.RKV_ERR_UNSUPPORTED
+    assert ws_status(lib, shape(lam=1.5))[0] == rkv.RKV_ERR_PARAM
+    assert ws_status(lib, shape(lam=float("nan")))[0] == rkv.RKV_ERR_PARAM
+    assert ws_status(lib, shape(sim_threshold=-0.1))[0] == rkv.RKV_ERR_PARAM
+    assert ws_status(lib, shape(beta=-1))[0] == rkv.RKV_ERR_PARAM
+    assert ws_status(lib, shape(pool_w=-1))[0] == rkv.RKV_ERR_PARAM
+    assert ws_status(lib, shape(eps=-1.0))[0] == rkv.RKV_ERR_PARAM
+    assert lib.rkv_workspace_size(None, ctypes.byref(ctypes.c_size_t(0))) == rkv.RKV_ERR_NULL
+
+
+def test_null_and_workspace_errors_return_before_any_launch(lib):
+    p = shape().params()
+    assert lib.rkv_compress(ctypes.byref(p), None, None, None, None, None, None, None, None, 0, None) == rkv.RKV_ERR_NULL
+    fake = ctypes.c_void_p(0x1000)        # never dereferenced: validation fails first
+    assert lib.rkv_compress(ctypes.byref(p), fake, fake, fake, fake, fake, None, None, None, 0, None) == rkv.RKV_ERR_WORKSPACE
+    assert lib.rkv_compress(ctypes.byref(p), fake, fake, fake, fake, fake, None, None, ctypes.c_void_p(0x1001), 1 << 40, None) == rkv.RKV_ERR_WORKSPACE
+    assert lib.rkv_compress(ctypes.byref(p), fake, fake, fake, fake, fake, None, None, fake, 16, None) == rkv.RKV_ERR_WORKSPACE
+    # cache does not exceed the budget: nothing to do (Alg. 1 early return)
+    p2 = shape(n_tokens=1024, budget=1024).params()
+    assert lib.rkv_compress(ctypes.byref(p2), fake, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == rkv.RKV_NOT_TRIGGERED
+    bad = shape().params()
+    bad.k_stride_token = 100
+    bad.k_stride_head = 8
+    bad.k_stride_problem = 8
+    assert lib.rkv_compress(ctypes.byref(bad), fake, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == rkv.RKV_ERR_SHAPE
+
+
+def test_status_strings(lib):
+    seen = {rkv.status_string(s) for s in range(-6, 2)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert rkv.status_string(99) == "unknown status"
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    s = shape(num_problems=1, kv_heads=1, q_heads=4, n_tokens=256, budget=128)
+    k = torch.zeros((1, 1, 256, 128), dtype=torch.bfloat16)
+    q = torch.zeros((1, 4, 8, 128), dtype=torch.bfloat16)
+    with pytest.raises(RuntimeError, match="no CPU path"):
+        rkv.rkv_compress(s, q, k, k)

@@ -1,0 +1,317 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Scores: |gpu - oracle| <= 1e-5 + 1e-3 |oracle| (rows whose threshold decision is within rounding
+of T are exempt).  Kept indices: exactly the top-k of the GPU's own scores under (score desc,
+index desc); against the oracle every candidate outside the tolerance band around the k-th score
+must agree.  Compacted K/V: bit-exact given the indices."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rkv_oracle as O
+from paper_2505_24133_amd import rkv, synth
+
+import helpers as Hp
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    rkv.load_library()
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+
+
+def dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def host_bits(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def shape_of(w: synth.Workload, P: int) -> rkv.Shape:
+    return rkv.Shape(num_problems=P, kv_heads=w.kv_heads, q_heads=w.q_heads, n_tokens=w.n_tokens,
+                     budget=w.budget, alpha=w.alpha, head_dim=w.head_dim, pool_w=w.pool_w, beta=w.beta,
+                     sim_threshold=w.sim_threshold, lam=w.lam, eps=w.eps)
+
+
+def check_head(w, ref, z_gpu, kept_gpu, kout, vout, kb, vb, tag, imp=None, red=None, msim=None):
+    """Compare one head's GPU results with the oracle's dict `ref`."""
+    n, k = w.n_cand, w.k_sel
+    kc = O.decode_bf16(kb[:n])
+    frag = Hp.fragile_rows(kc, float(np.float32(w.sim_threshold)), w.beta, w.eps)
+    ok = ~frag
+    if imp is not None:
+        assert Hp.close(imp, ref["importance"]).all(), f"{tag}: importance"
+    if msim is not None:
+        bad = ~Hp.close(msim[ok], ref["mean_sim"][ok], rel=1e-3, abs_=2e-6)
+        assert not bad.any(), f"{tag}: mean_sim, {bad.sum()} rows, max abs {np.abs(msim[ok] - ref['mean_sim'][ok]).max()}"
+    if red is not None:
+        assert Hp.close(red[ok], ref["redundancy"][ok]).all(), f"{tag}: redundancy"
+    if z_gpu is not None:
+        assert Hp.close(z_gpu[ok], ref["score"][ok]).all(), f"{tag}: score"
+        # much sharper than the contract: relative error of the fp32 pipeline
+        err = Hp.max_rel_err(z_gpu[ok], ref["score"][ok])
+        assert err < 2e-4, f"{tag}: score rel err {err}"
+    if kept_gpu is not None:
+        sel = kept_gpu[:k].astype(np.int64)
+        assert np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] < n, f"{tag}: kept order/range"
+        np.testing.assert_array_equal(kept_gpu[k:], np.arange(n, w.n_tokens), err_msg=f"{tag}: observation rows")
+        if z_gpu is not None:
+            np.testing.assert_array_equal(sel, Hp.exact_topk(z_gpu, k), err_msg=f"{tag}: not the top-k of its own score")
+        mk, md, free = Hp.check_kept_against_oracle(sel, ref["score"], k, frag)
+        assert mk == 0 and md == 0, f"{tag}: kept set vs oracle: {mk} missing, {md} extra (free {free})"
+        if kout is not None:
+            np.testing.assert_array_equal(kout, kb[kept_gpu], err_msg=f"{tag}: K_out")
+            np.testing.assert_array_equal(vout, vb[kept_gpu], err_msg=f"{tag}: V_out")
+    return int(frag.sum())
+
+
+def run_fused(w, q, k, v, heads, tag, check_parts=False):
+    """q,k,v: uint16 [P,...].  Runs rkv_compress (and optionally every stand-alone entry point) and
+    checks the listed (p, h) heads against the oracle."""
+    P = k.shape[0]
+    shp = shape_of(w, P)
+    say(f"{tag}: rkv_compress P={P} H={w.kv_heads} N={w.n_tokens} budget={w.budget} G={w.group} "
+        f"alpha={w.alpha} W={w.pool_w} beta={w.beta} T={w.sim_threshold} lam={w.lam}")
+    qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    st, ko, vo, idx, score = rkv.rkv_compress(shp, qd, kd, vd, want_idx=True, want_score=True)
+    torch.cuda.synchronize()
+    assert st == rkv.RKV_OK
+    parts = None
+    if check_parts:
+        say(f"{tag}: stand-alone entry points")
+        imp = rkv.rkv_score_importance(shp, qd, kd)
+        red, msim = rkv.rkv_score_redundancy(shp, kd, want_mean_sim=True)
+        kept2, score2 = rkv.rkv_select_topk(shp, imp, red, want_score=True)
+        ko2, vo2 = rkv.rkv_compact(shp, kd, vd, kept2)
+        torch.cuda.synchronize()
+        assert torch.equal(kept2, idx) and torch.equal(score2, score), f"{tag}: fused != staged"
+        assert torch.equal(ko2, ko) and torch.equal(vo2, vo)
+        parts = (imp.cpu().numpy(), red.cpu().numpy(), msim.cpu().numpy())
+    ko_h, vo_h = host_bits(ko), host_bits(vo)
+    idx_h, score_h = idx.cpu().numpy(), score.cpu().numpy()
+    prm = Hp.oracle_params(w)
+    G = w.group
+    nfrag = 0
+    for (p, h) in heads:
+        ref = O.compress_head(q[p, h * G:(h + 1) * G], k[p, h], v[p, h], prm)
+        extra = {}
+        if parts is not None:
+            extra = dict(imp=parts[0][p, h], red=parts[1][p, h], msim=parts[2][p, h])
+        nfrag += check_head(w, ref, score_h[p, h], idx_h[p, h], ko_h[p, h], vo_h[p, h], k[p, h], v[p, h],
+                            f"{tag}[p{p},h{h}]", **extra)
+    say(f"{tag}: {len(heads)} heads match ({nfrag} threshold-fragile rows exempt)")
+    return idx, score, ko, vo
+
+
+# ------------------------------------------------------------------------------ configs
+def test_cfg1_tiny_all_entry_points():
+    w = synth.CONFIGS["cfg1_tiny"]
+    q, k, v = synth.make_batch(w)
+    run_fused(w, q, k, v, [(0, 0), (0, 1)], "cfg1", check_parts=True)
+
+
+ADVERSARIAL = [
+    # N, budget, kv_heads, G, alpha, W, beta, T, lam
+    (203, 120, 2, 4, 8, 4, 1, 0.5, 0.1),      # ragged: n = 195 is no multiple of any tile
+    (129, 100, 1, 1, 8, 0, 0, 0.5, 0.1),      # MHA, no pooling, nothing forgiven
+    (300, 40, 2, 5, 8, 1, 2, 0.3, 0.1),       # G = 5 (40 query rows -> two MFMA row tiles)
+    (260, 250, 2, 4, 1, 2, 8, 0.95, 0.5),     # alpha = 1, few evictions
+    (452, 300, 1, 5, 12, 7, 1, 1.0, 0.0),     # 60 query rows, T = 1 (never exceeded), lambda = 0
+    (577, 320, 3, 2, 8, 4, 4, 0.0, 1.0),      # T = 0: every positive similarity is a hit; lambda = 1
+    (65, 17, 2, 4, 8, 4, 1, 0.5, 0.1),        # smaller than one tile
+    (1030, 999, 1, 4, 8, 16, 3, 0.8, 0.05),   # wide pooling window
+]
+
+
+@pytest.mark.parametrize("case", ADVERSARIAL, ids=lambda c: f"N{c[0]}_b{c[1]}_G{c[3]}_a{c[4]}_W{c[5]}_beta{c[6]}_T{c[7]}")
+def test_adversarial_shapes(case):
+    N, budget, H, G, alpha, W, beta, T, lam = case
+    w = synth.Workload("adv", 2, H, H * G, N, budget, alpha=alpha, pool_w=W, beta=beta, sim_threshold=T,
+                       lam=lam, seed=77 + N, recipe="rowcopy", redundancy=0.35, copy_noise=0.15)
+    q, k, v = synth.make_batch(w)
+    run_fused(w, q, k, v, [(p, h) for p in range(2) for h in range(H)], f"adv{N}", check_parts=True)
+
+
+def test_cfg2_llama8b_full_size_all_heads():
+    w = synth.CONFIGS["cfg2_llama8b_b1024"]
+    q, k, v = synth.make_batch(w)
+    run_fused(w, q, k, v, [(p, h) for p in range(w.num_problems) for h in range(w.kv_heads)], "cfg2")
+
+
+def test_cfg2_high_threshold():
+    """T = 0.95: only true near-duplicates exceed the threshold, most rows never saturate."""
+    w = synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], sim_threshold=0.95, num_problems=4)
+    q, k, v = synth.make_batch(w)
+    run_fused(w, q, k, v, [(p, h) for p in range(4) for h in range(0, 8, 3)], "cfg2_T095", check_parts=True)
+
+
+def test_cfg3_llama8b_budget4096_full_size_sampled_heads():
+    w = synth.CONFIGS["cfg3_llama8b_b4096"]
+    q, k, v = synth.make_batch(w)
+    heads = [(0, 0), (7, 3), (13, 5), (21, 1), (31, 7), (16, 6)]
+    run_fused(w, q, k, v, heads, "cfg3")
+
+
+def _replicated(w, distinct, reps):
+    q, k, v = synth.make_batch(w, distinct)
+    return np.tile(q, (reps, 1, 1, 1)), np.tile(k, (reps, 1, 1, 1)), np.tile(v, (reps, 1, 1, 1))
+
+
+def test_cfg4_qwen14b_full_size_launch():
+    """P = 768 as in the config; to keep host generation short the 16 sequences' first layers are
+    drawn and repeated over the 48 layer slots (the launch shape and every kernel's grid are the
+    full-size ones)."""
+    w = synth.CONFIGS["cfg4_qwen14b_b2048_bs16"]
+    distinct = [s * w.layers for s in range(16)]
+    q, k, v = _replicated(w, distinct, w.layers)
+    assert k.shape[0] == w.num_problems
+    heads = [(0, 0), (5, 7), (15, 3), (16 * 20 + 9, 4), (767, 7), (400, 2)]
+    idx, score, ko, vo = run_fused(w, q, k, v, heads, "cfg4")
+    # replicas of a problem give bit-identical results wherever they sit in the grid
+    assert torch.equal(idx[:16], idx[16 * 47:16 * 48]) and torch.equal(score[:16], score[16 * 30:16 * 31])
+    assert torch.equal(ko[:16], ko[16 * 47:16 * 48])
+
+
+def test_cfg5_long_trace_full_size_launch():
+    w = synth.CONFIGS["cfg5_llama8b_b8192_bs4"]
+    distinct = [s * w.layers for s in range(4)]
+    q, k, v = _replicated(w, distinct, w.layers)
+    assert k.shape[0] == w.num_problems
+    heads = [(0, 0), (3, 7), (4 * 31 + 2, 5)]
+    idx, score, ko, vo = run_fused(w, q, k, v, heads, "cfg5")
+    assert torch.equal(idx[:4], idx[124:128]) and torch.equal(vo[:4], vo[64:68])
+
+
+# --------------------------------------------------------------------------- properties
+def test_bit_identical_on_repeat_and_on_another_stream():
+    w = synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=3)
+    q, k, v = synth.make_batch(w)
+    shp = shape_of(w, 3)
+    qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    say("repeat: default stream twice, then a side stream")
+    a = rkv.rkv_compress(shp, qd, kd, vd, want_score=True)
+    b = rkv.rkv_compress(shp, qd, kd, vd, want_score=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        c = rkv.rkv_compress(shp, qd, kd, vd, want_score=True)
+    side.synchronize()
+    torch.cuda.synchronize()
+    for other in (b, c):
+        for x, y in zip(a[1:], other[1:]):
+            assert torch.equal(x, y)
+
+
+def test_strided_cache_views():
+    """K/V given as views of a larger [P, H, N_alloc, d] allocation (static cache with spare rows)."""
+    w = synth.scaled(synth.CONFIGS["cfg1_tiny"], num_problems=2, kv_heads=2)
+    q, k, v = synth.make_batch(w)
+    shp = shape_of(w, 2)
+    qd = dev_bf16(q)
+    big_k = torch.zeros((2, 2, w.n_tokens + 40, 128), dtype=torch.bfloat16, device="cuda")
+    big_v = torch.zeros((2, 2, w.n_tokens + 72, 128), dtype=torch.bfloat16, device="cuda")
+    big_k[:, :, :w.n_tokens] = dev_bf16(k)
+    big_v[:, :, :w.n_tokens] = dev_bf16(v)
+    say("strided views")
+    a = rkv.rkv_compress(shp, qd, big_k[:, :, :w.n_tokens], big_v[:, :, :w.n_tokens], want_score=True)
+    b = rkv.rkv_compress(shp, qd, dev_bf16(k), dev_bf16(v), want_score=True)
+    torch.cuda.synchronize()
+    for x, y in zip(a[1:], b[1:]):
+        assert torch.equal(x, y)
+
+
+def test_exact_duplicates_only_one_copy_survives():
+    """m exact copies of one key among otherwise orthogonal keys, lambda = 0, m - 1 evictions:
+    the older copies go and the newest stays (tie-break towards the recent token)."""
+    m, alpha, n = 4, 8, 120
+    N = n + alpha
+    kf = np.zeros((1, 1, N, 128), dtype=np.float32)
+    pos = [5, 40, 77, 101]
+    free = iter(range(1, 128))
+    for i in range(N):
+        if i in pos:
+            kf[0, 0, i, 0] = 2.0
+        else:
+            kf[0, 0, i, next(free) if i < 120 else 127 - (i - 120)] = 1.0 + 0.01 * i
+    rng = np.random.default_rng(5)
+    q = synth.f32_to_bf16_bits(rng.standard_normal((1, 4, alpha, 128)).astype(np.float32))
+    k = synth.f32_to_bf16_bits(kf)
+    v = synth.f32_to_bf16_bits(rng.standard_normal((1, 1, N, 128)).astype(np.float32))
+    w = synth.Workload("dups", 1, 1, 4, N, n - (m - 1) + alpha, alpha=alpha, pool_w=0, beta=1,
+                       sim_threshold=0.5, lam=0.0)
+    idx, score, ko, vo = run_fused(w, q, k, v, [(0, 0)], "dups")
+    kept = set(idx[0, 0].cpu().numpy().tolist())
+    assert [p in kept for p in pos] == [False, False, False, True]
+
+
+def test_lambda_one_is_attention_only_selection():
+    w = synth.scaled(synth.CONFIGS["cfg1_tiny"], lam=1.0)
+    q, k, v = synth.make_batch(w)
+    shp = shape_of(w, 1)
+    qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    say("lambda = 1")
+    imp = rkv.rkv_score_importance(shp, qd, kd)
+    st, ko, vo, idx, score = rkv.rkv_compress(shp, qd, kd, vd, want_score=True)
+    torch.cuda.synchronize()
+    assert torch.equal(imp, score)
+    for h in range(w.kv_heads):
+        np.testing.assert_array_equal(idx[0, h, :w.k_sel].cpu().numpy(), Hp.exact_topk(imp[0, h].cpu().numpy(), w.k_sel))
+
+
+def test_select_topk_ties_and_maximum_size():
+    """rkv_select_topk alone: heavy ties, all-equal scores, and the largest supported N."""
+    for (N, budget, levels) in [(32768, 20000, 7), (32768, 32000, 1), (5000, 4999, 3), (600, 9, 2)]:
+        alpha = 8
+        n = N - alpha
+        shp = rkv.Shape(num_problems=1, kv_heads=3, q_heads=3, n_tokens=N, budget=budget, alpha=alpha, lam=0.25)
+        g = torch.Generator().manual_seed(N + levels)
+        imp = torch.randint(0, levels, (1, 3, n), generator=g).float() / 64.0
+        red = torch.randint(0, levels, (1, 3, n), generator=g).float() / 64.0
+        say(f"select N={N} budget={budget} levels={levels}")
+        kept, score = rkv.rkv_select_topk(shp, imp.cuda(), red.cuda(), want_score=True)
+        torch.cuda.synchronize()
+        z = score.cpu().numpy()
+        zr = np.float32(0.25) * imp.numpy() - (np.float32(1.0) - np.float32(0.25)) * red.numpy()
+        np.testing.assert_allclose(z, zr, rtol=1e-6, atol=1e-9)
+        for h in range(3):
+            kh = kept[0, h].cpu().numpy()
+            np.testing.assert_array_equal(kh[:budget - alpha], Hp.exact_topk(z[0, h], budget - alpha))
+            np.testing.assert_array_equal(kh[budget - alpha:], np.arange(n, N))
+
+
+def test_compact_arbitrary_indices():
+    P, H, N, budget = 2, 3, 500, 333
+    shp = rkv.Shape(num_problems=P, kv_heads=H, q_heads=H, n_tokens=N, budget=budget)
+    g = torch.Generator().manual_seed(3)
+    k = torch.randn((P, H, N, 128), generator=g).to(torch.bfloat16).cuda()
+    v = torch.randn((P, H, N, 128), generator=g).to(torch.bfloat16).cuda()
+    idx = torch.randint(0, N, (P, H, budget), generator=g, dtype=torch.int32)
+    idx[0, 0, 0] = -5          # clamped to 0
+    idx[1, 2, 7] = N + 100     # clamped to N - 1
+    say("compact")
+    ko, vo = rkv.rkv_compact(shp, k, v, idx.cuda())
+    torch.cuda.synchronize()
+    ci = idx.clamp(0, N - 1).long().cuda()
+    ref_k = torch.gather(k, 2, ci[..., None].expand(-1, -1, -1, 128))
+    ref_v = torch.gather(v, 2, ci[..., None].expand(-1, -1, -1, 128))
+    assert torch.equal(ko, ref_k) and torch.equal(vo, ref_v)
+
+
+def test_not_triggered_leaves_outputs_untouched():
+    shp = rkv.Shape(num_problems=1, kv_heads=2, q_heads=8, n_tokens=256, budget=256)
+    k = torch.randn((1, 2, 256, 128)).to(torch.bfloat16).cuda()
+    q = torch.randn((1, 8, 8, 128)).to(torch.bfloat16).cuda()
+    ko = torch.full((1, 2, 256, 128), 7.0, dtype=torch.bfloat16, device="cuda")
+    vo = ko.clone()
+    say("not triggered")
+    st, ko2, vo2, idx, _ = rkv.rkv_compress(shp, q, k, k, k_out=ko, v_out=vo)
+    torch.cuda.synchronize()
+    assert st == rkv.RKV_NOT_TRIGGERED
+    assert bool((ko == 7.0).all()) and bool((vo == 7.0).all())
