@@ -55,9 +55,11 @@ def check_head(w, ref, z_gpu, kept_gpu, kout, vout, kb, vb, tag, imp=None, red=N
         assert Hp.close(red[ok], ref["redundancy"][ok]).all(), f"{tag}: redundancy"
     if z_gpu is not None:
         assert Hp.close(z_gpu[ok], ref["score"][ok]).all(), f"{tag}: score"
-        # much sharper than the contract: relative error of the fp32 pipeline
-        err = Hp.max_rel_err(z_gpu[ok], ref["score"][ok])
-        assert err < 2e-4, f"{tag}: score rel err {err}"
+        # much sharper than the contract: error relative to the size of the two terms of Eq. 7
+        lam = float(np.float32(w.lam))
+        scale = lam * np.abs(ref["importance"]) + (1 - lam) * np.abs(ref["redundancy"])
+        err = np.max(np.abs(z_gpu.astype(np.float64) - ref["score"])[ok] / (scale[ok] + 1e-12))
+        assert err < 5e-5, f"{tag}: score err relative to its terms {err}"
     if kept_gpu is not None:
         sel = kept_gpu[:k].astype(np.int64)
         assert np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] < n, f"{tag}: kept order/range"
