@@ -19,10 +19,11 @@
  *     and the call returns without synchronising the device.
  *   - `ws` is caller-provided device scratch of at least rkv_workspace_size() bytes,
  *     256-byte aligned; contents need not be preserved between calls.
- *   - Errors are returned as negative rkv_status values; when a negative status is returned
- *     nothing has been enqueued and the outputs are untouched.
+ *   - Errors are returned as negative rkv_status values.  Arguments are validated before the
+ *     first launch: for every negative status except RKV_ERR_HIP nothing has been enqueued and
+ *     the outputs are untouched (after RKV_ERR_HIP earlier stages of the call may have run).
  *   - Inputs holding NaN or Inf give unspecified scores (never out-of-bounds accesses).
- *   - Supported shapes: d == 128, 1 <= alpha <= 64, G * alpha <= 64, N <= 65536,
+ *   - Supported shapes: d == 128, 1 <= alpha <= 64, G * alpha <= 64, N <= 32768,
  *     token strides multiples of 8 elements (16-byte aligned rows).
  */
 #ifndef RKV_H
@@ -37,7 +38,7 @@ extern "C" {
 
 typedef enum {
   RKV_OK = 0,
-  RKV_NOT_TRIGGERED = 1,     /* n <= budget - alpha... i.e. N <= budget: nothing to evict (Alg. 1 early returns) */
+  RKV_NOT_TRIGGERED = 1,     /* N <= budget: nothing to evict, nothing enqueued (the early returns of Alg. 1) */
   RKV_ERR_NULL = -1,         /* a required pointer is NULL */
   RKV_ERR_SHAPE = -2,        /* inconsistent sizes: q_heads % kv_heads, budget <= alpha, N <= alpha, strides */
   RKV_ERR_UNSUPPORTED = -3,  /* outside the supported shapes listed above, or unknown flag bits */
@@ -112,6 +113,16 @@ rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, cons
 rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
                         void* k_out, void* v_out, int32_t* kept_idx, float* score,
                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Instrumented form of rkv_compress for measurement: identical work, and additionally records the
+ * five caller-created hipEvent_t handles events[0..4] (a HOST array) on `stream` before the key
+ * pre-pass and after the pre-pass, the similarity pass, the finalize/select kernel and the gather,
+ * so that hipEventElapsedTime(events[i], events[i+1]) is the duration of stage i.
+ */
+rkv_status rkv_compress_events(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
+                               void* k_out, void* v_out, int32_t* kept_idx, float* score,
+                               void* ws, size_t ws_bytes, void* stream, void* const* events);
 
 /* Static, NUL-terminated description of a status value. */
 const char* rkv_status_string(rkv_status s);

@@ -132,9 +132,9 @@ rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, cons
   return hip_status(launch_gather(pl, k, v, kept_idx, k_out, v_out, static_cast<hipStream_t>(stream)));
 }
 
-rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
-                        void* k_out, void* v_out, int32_t* kept_idx, float* score,
-                        void* ws, size_t ws_bytes, void* stream) {
+static rkv_status compress_impl(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
+                                void* k_out, void* v_out, int32_t* kept_idx, float* score,
+                                void* ws, size_t ws_bytes, void* stream, void* const* events) {
   if (q_obs == nullptr || k == nullptr || v == nullptr || k_out == nullptr || v_out == nullptr) return RKV_ERR_NULL;
   Plan pl;
   rkv_status s = make_plan(prm, &pl);
@@ -144,12 +144,36 @@ rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k,
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* w = static_cast<char*>(ws);
   int32_t* idx = kept_idx ? kept_idx : reinterpret_cast<int32_t*>(w + pl.off_idx);
+  auto mark = [&](int i) -> rkv_status {
+    if (events == nullptr) return RKV_OK;
+    return hip_status(hipEventRecord(static_cast<hipEvent_t>(events[i]), st));
+  };
+  if ((s = mark(0)) != RKV_OK) return s;
   if ((s = hip_status(launch_prepass(pl, q_obs, k, w, st))) != RKV_OK) return s;
+  if ((s = mark(1)) != RKV_OK) return s;
   if ((s = hip_status(launch_gram(pl, k, w, st))) != RKV_OK) return s;
+  if ((s = mark(2)) != RKV_OK) return s;
   if ((s = hip_status(launch_finalize(pl, kModeImportance | kModeRedundancy | kModeSelect, w, nullptr, nullptr,
                                       nullptr, nullptr, nullptr, score, idx, st))) != RKV_OK)
     return s;
-  return hip_status(launch_gather(pl, k, v, idx, k_out, v_out, st));
+  if ((s = mark(3)) != RKV_OK) return s;
+  if ((s = hip_status(launch_gather(pl, k, v, idx, k_out, v_out, st))) != RKV_OK) return s;
+  return mark(4);
+}
+
+rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
+                        void* k_out, void* v_out, int32_t* kept_idx, float* score,
+                        void* ws, size_t ws_bytes, void* stream) {
+  return compress_impl(prm, q_obs, k, v, k_out, v_out, kept_idx, score, ws, ws_bytes, stream, nullptr);
+}
+
+rkv_status rkv_compress_events(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
+                               void* k_out, void* v_out, int32_t* kept_idx, float* score,
+                               void* ws, size_t ws_bytes, void* stream, void* const* events) {
+  if (events == nullptr) return RKV_ERR_NULL;
+  for (int i = 0; i < 5; ++i)
+    if (events[i] == nullptr) return RKV_ERR_NULL;
+  return compress_impl(prm, q_obs, k, v, k_out, v_out, kept_idx, score, ws, ws_bytes, stream, events);
 }
 
 const char* rkv_status_string(rkv_status s) {

@@ -63,8 +63,9 @@ def load_library() -> ctypes.CDLL:
     lib.rkv_select_topk.argtypes = [P, V, V, V, V, V, S, V]
     lib.rkv_compact.argtypes = [P, V, V, V, V, V, V]
     lib.rkv_compress.argtypes = [P, V, V, V, V, V, V, V, V, S, V]
+    lib.rkv_compress_events.argtypes = [P, V, V, V, V, V, V, V, V, S, V, ctypes.POINTER(ctypes.c_void_p)]
     for name in ("rkv_workspace_size", "rkv_score_importance", "rkv_score_redundancy", "rkv_select_topk",
-                 "rkv_compact", "rkv_compress"):
+                 "rkv_compact", "rkv_compress", "rkv_compress_events"):
         getattr(lib, name).restype = ctypes.c_int
     lib.rkv_status_string.argtypes = [ctypes.c_int]
     lib.rkv_status_string.restype = ctypes.c_char_p
@@ -225,9 +226,11 @@ def rkv_compact(shape: Shape, k: torch.Tensor, v: torch.Tensor, kept_idx: torch.
 def rkv_compress(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
                  ws: Optional[torch.Tensor] = None, k_out: Optional[torch.Tensor] = None,
                  v_out: Optional[torch.Tensor] = None, kept_idx: Optional[torch.Tensor] = None,
-                 score: Optional[torch.Tensor] = None, want_idx: bool = True, want_score: bool = False):
+                 score: Optional[torch.Tensor] = None, want_idx: bool = True, want_score: bool = False,
+                 events=None):
     """The whole step.  Returns (status, k_out, v_out, kept_idx, score); status is RKV_OK or
-    RKV_NOT_TRIGGERED (then nothing was computed)."""
+    RKV_NOT_TRIGGERED (then nothing was computed).  `events`, if given, is a ctypes array of five
+    hipEvent_t handles recorded around the four stages (rkv_compress_events)."""
     _need_gpu(q_obs, k, v)
     _check_q(shape, q_obs)
     _check_kv(shape, k, "k")
@@ -244,8 +247,13 @@ def rkv_compress(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Te
         score = torch.empty((shape.num_problems, shape.kv_heads, shape.n_cand), dtype=torch.float32, device=dev)
     ws, wp, wb = _ws_args(shape, ws, dev)
     prm = shape.params(k, v)
-    s = load_library().rkv_compress(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out),
-                                    _ptr(kept_idx), _ptr(score), wp, wb, _stream())
+    lib = load_library()
+    if events is None:
+        s = lib.rkv_compress(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out),
+                             _ptr(kept_idx), _ptr(score), wp, wb, _stream())
+    else:
+        s = lib.rkv_compress_events(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out),
+                                    _ptr(kept_idx), _ptr(score), wp, wb, _stream(), events)
     if s < 0:
         raise RkvError(s, "rkv_compress")
     return s, k_out, v_out, kept_idx, score

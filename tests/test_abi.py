@@ -25,11 +25,11 @@ def declared_symbols(repo_root):
 
 def test_every_declared_symbol_is_exported(lib, repo_root):
     names = declared_symbols(repo_root)
-    assert names == ["rkv_compact", "rkv_compress", "rkv_score_importance", "rkv_score_redundancy",
+    assert names == ["rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_score_importance", "rkv_score_redundancy",
                      "rkv_select_topk", "rkv_status_string", "rkv_workspace_size"]
     for n in names:
         assert hasattr(lib, n), n
-    assert set(rkv.__dict__) >= set(names) - {"rkv_status_string"}
+    assert set(rkv.__dict__) >= set(names) - {"rkv_status_string", "rkv_compress_events"}
 
 
 def test_params_struct_layout_matches_header():
