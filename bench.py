@@ -70,6 +70,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sim-threshold", type=float, default=None)
+    ap.add_argument("--beta", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (heads shard across GPUs with no exchange; "
@@ -86,6 +87,8 @@ def main() -> int:
     w = synth.CONFIGS[args.workload]
     if args.sim_threshold is not None:
         w = synth.scaled(w, sim_threshold=args.sim_threshold)
+    if args.beta is not None:
+        w = synth.scaled(w, beta=args.beta)
     q, k, v = synth.make_batch(w)
 
     def dev(bits):

@@ -35,7 +35,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
       *ot = kHeadDim; *oh = (int64_t)q.n_tokens * kHeadDim; *op = *oh * q.kv_heads;
       return true;
     }
-    if (st < kHeadDim || (st % 8) != 0 || (sh % 8) != 0 || (sp % 8) != 0 || sh < 0 || sp < 0) return false;
+    if (st < kHeadDim || st > 32768 || (st % 8) != 0 || (sh % 8) != 0 || (sp % 8) != 0 || sh < 0 || sp < 0) return false;
     if (q.kv_heads > 1 && sh == 0) return false;
     if (q.num_problems > 1 && sp == 0) return false;
     *op = sp; *oh = sh; *ot = st;

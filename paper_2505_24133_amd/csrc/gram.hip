@@ -10,17 +10,21 @@
 // Column tiles are visited in DESCENDING j, so the first beta hits a row meets are its beta
 // most recent similar tokens; a row that has met beta hits gets threshold +inf.
 //
-// Work split: a workgroup owns 64 * NW consecutive rows (each wave 64 rows, held as MFMA A
-// fragments in registers for the whole pass) and streams all column tiles (64 keys) of the
-// head through double-buffered LDS.  Per 32x32 tile the common-case epilogue is one FMA per
-// element (acc * r_j - T / r_i) folded into a running max, then one wave-wide test.
+// Work split: a workgroup owns NW * RT * 32 consecutive rows.  Each wave keeps its RT * 32 rows as
+// the MFMA *B* operand in registers for the whole pass, so a lane owns ONE row per row tile and
+// the row's state (threshold T / r_i, hits taken, forgiven sum) lives in three registers.  The
+// head's keys stream through double-buffered LDS as the MFMA *A* operand in tiles of TC keys,
+// copied global -> LDS by the DMA path (no staging registers) into an XOR-swizzled layout that
+// the 16-byte fragment reads hit without bank conflicts.  Per 32x32 tile the common-case
+// epilogue is one multiply per element folded into a running max, issued in the shadow of the
+// next tile's MFMA chain; K_i . u comes from three extra pseudo-keys (u split into bf16 pieces).
 #include "rkv_internal.h"
 
 namespace rkv {
 
 namespace {
 
-constexpr int kTileCols = 64;
+extern __shared__ __attribute__((aligned(1024))) unsigned char gram_lds[];
 
 struct GramArgs {
   const uint16_t* k;
@@ -32,19 +36,41 @@ struct GramArgs {
   float T, eps;
 };
 
-template <int NW>
-__global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
-  constexpr int NT = NW * 64;
-  constexpr int BM = NW * 64;
-  constexpr int PIECES = kTileCols * 16;                  // 16-byte pieces per column tile
-  constexpr int LPT = (PIECES + NT - 1) / NT;             // pieces per thread
+constexpr int kPseudoBytes = 3 * kRowBytes;     // u as three bf16 pseudo-keys
 
-  __shared__ __attribute__((aligned(16))) unsigned char kt[2][kTileCols * kLdsRowBytes];
-  __shared__ float rjl[2][kTileCols];
-  __shared__ float ul[kHeadDim];
-  __shared__ float rowdot[BM];
-  __shared__ float sub[BM];
-  __shared__ int cnt[BM];
+// 16-byte slot of (row, chunk) inside a tile: rows are 256 bytes, chunks XOR-swizzled by the row, so
+// that 16 consecutive rows read at the same chunk fall into 16 different bank groups.
+__device__ __forceinline__ int slot_offset(int row, int chunk) { return row * kRowBytes + ((chunk ^ (row & 15)) << 4); }
+
+// One wave-wide DMA copy: lane l fetches 16 bytes at base + voff and the hardware stores them
+// at LDS address lds_base + 16 * l.  Issued as inline assembly so that the compiler does not
+// serialise later LDS reads of the *other* buffer behind it; completion is awaited explicitly
+// (vmcnt) before the barrier that publishes the buffer.
+__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_base), "v"(voff), "s"(base)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2"
+               :
+               : "s"(lds_base), "v"(voff), "s"(base)
+               : "memory", "m0");
+}
+
+template <int NW, int RT, int TC>
+__global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
+  constexpr int BM = NW * RT * 32;
+  constexpr int NS = TC / 32;                       // 32-key subtiles per tile
+  constexpr int LOADS = TC / 4;                     // wave-wide DMA copies per tile (4 rows each)
+  static_assert(NW == 2 || NW == 4, "the DMA split assumes 2 or 4 waves");
+  static_assert(RT >= 2, "the r_j prefetch needs at least two row tiles per wave");
+  static_assert(LOADS % NW == 0, "tile rows must split evenly over the waves");
+  // LDS map: [pseudo-keys | tile 0 | tile 1 | r_j of tile 0 | r_j of tile 1]
+  constexpr int OFF_TILE = kPseudoBytes;
+  constexpr int TILE_SPAN = LOADS * 1024;            // bytes the DMA copies of one tile cover
+  constexpr int OFF_RJ = OFF_TILE + 2 * TILE_SPAN;
 
   // Workgroups are dealt round-robin to the 8 XCDs; give every XCD whole heads so that a head's
   // keys are fetched into one L2 only.
@@ -65,157 +91,218 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
   const uint16_t* kbase = a.k + p * a.ksp + h * a.ksh;
   const float* rn = a.rnorm + (int64_t)head * a.n_pad;
   const int n = a.n;
-  const int i0 = rb * BM + wave * 64;
+  const int i0 = rb * BM + wave * (RT * 32);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)gram_lds;   // LDS byte address of the dynamic segment
+  const uint32_t row_bytes = (uint32_t)a.kst * 2u;
 
-  // ---- prologue
+  // Copy tile `ct` (keys ct*TC ...) and its r_j into buffer `buf`.  Keys past n are read from
+  // row n-1 (any finite row will do: their r_j is 0).
+  auto issue_tile = [&](int ct, int buf) {
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + OFF_TILE + buf * TILE_SPAN + wave * 1024);
+#pragma unroll
+    for (int jj = 0; jj < LOADS / NW; ++jj) {
+      const int row = (wave + jj * NW) * 4 + (lane >> 4);     // row inside the tile
+      const int key = min(ct * TC + row, n - 1);
+      const int chunk = (lane & 15) ^ (row & 15);            // the chunk that belongs in this lane's slot
+      dma16(kbase, (uint32_t)key * row_bytes + (uint32_t)chunk * 16u, dst + jj * NW * 1024);
+    }
+    if (wave < TC / 64)
+      dma4(rn + ct * TC, (uint32_t)(wave * 64 + lane) * 4u,
+           __builtin_amdgcn_readfirstlane(lds0 + OFF_RJ + buf * TC * 4 + wave * 256));
+  };
+  const int nct = (a.beta > 0) ? (n + TC - 1) / TC : 0;
+  if (nct > 0) issue_tile(nct - 1, 0);
+
+  // ---- prologue: u -> three bf16 pseudo-keys, the wave's rows -> registers
   if (t < kHeadDim) {
     const float* up = a.upart + (int64_t)head * a.chunks * kHeadDim + t;
-    float s = 0.f;
-    for (int c = 0; c < a.chunks; ++c) s += up[(int64_t)c * kHeadDim];
-    ul[t] = s;
-  }
-  for (int i = t; i < BM; i += NT) { sub[i] = 0.f; cnt[i] = 0; }
-
-  bf16x8 af[2][8];
+    float u = 0.f;
+    for (int c = 0; c < a.chunks; ++c) u += up[(int64_t)c * kHeadDim];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) {
+    for (int piece = 0; piece < 3; ++piece) {
+      uint32_t bits = __float_as_uint(u);
+      bits += 0x7fffu + ((bits >> 16) & 1u);                  // round to nearest even bf16
+      const uint16_t hb = (uint16_t)(bits >> 16);
+      u -= __uint_as_float((uint32_t)hb << 16);               // exact remainder
+      *reinterpret_cast<uint16_t*>(gram_lds + slot_offset(piece, t >> 3) + (t & 7) * 2) = hb;
+    }
+  }
+  bf16x8 res[RT][8];
+  float thr[RT], sub[RT], rowdot[RT];
+  int cnt[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
     const int row = i0 + rt * 32 + lrow;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       uint4 x = make_uint4(0, 0, 0, 0);
       if (row < n) x = *reinterpret_cast<const uint4*>(kbase + (int64_t)row * a.kst + kk * 16 + half * 8);
-      __builtin_memcpy(&af[rt][kk], &x, 16);
+      __builtin_memcpy(&res[rt][kk], &x, 16);
     }
+    thr[rt] = (row < n && a.beta > 0) ? a.T / rn[row] : INFINITY;
+    sub[rt] = 0.f;
+    cnt[rt] = 0;
   }
-  float thr[2][16];
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = i0 + rt * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-      thr[rt][i] = (row < n && a.beta > 0) ? a.T / rn[row] : INFINITY;
-    }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  // K_i . u for the wave's 64 rows (each lane holds half of a row's elements)
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt) {
-    float s = 0.f;
+
+  // 16-byte A-operand fragments of subtile s: key row lane%32, k-slice (kk, lane/32)
+  auto read_k = [&](bf16x8 (&kf)[8], const unsigned char* tile, int s) {
+    const int row = s * 32 + lrow;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk)
+      kf[kk] = *reinterpret_cast<const bf16x8*>(tile + slot_offset(row, kk * 2 + half));
+  };
+  // r_j of the 16 keys this lane sees in its accumulator: key = 8*(i/4) + 4*half + i%4
+  auto read_rj = [&](float (&rj)[16], const float* rjs, int s) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s = fmaf((float)af[rt][kk][e], ul[kk * 16 + half * 8 + e], s);
-    s += __shfl_xor(s, 32);
-    if (half == 0) rowdot[wave * 64 + rt * 32 + lrow] = s;
-  }
-
-  // ---- stream the column tiles, most recent first
-  const int nct = (a.beta > 0) ? (n + kTileCols - 1) / kTileCols : 0;
-  uint4 stage[LPT];
-  float stage_r = 0.f;
-  auto load_tile = [&](int ct) {
-#pragma unroll
-    for (int m = 0; m < LPT; ++m) {
-      const int piece = t + m * NT;
-      const int row = piece >> 4, c16 = piece & 15;
-      const int grow = ct * kTileCols + row;
-      stage[m] = make_uint4(0, 0, 0, 0);
-      if (piece < PIECES && grow < n)
-        stage[m] = *reinterpret_cast<const uint4*>(kbase + (int64_t)grow * a.kst + c16 * 8);
-    }
-    if (t < kTileCols) {
-      const int grow = ct * kTileCols + t;
-      stage_r = (grow < n) ? rn[grow] : 0.f;
+    for (int g = 0; g < 4; ++g) {
+      const float4 v = *reinterpret_cast<const float4*>(rjs + s * 32 + g * 8 + half * 4);
+      rj[4 * g] = v.x; rj[4 * g + 1] = v.y; rj[4 * g + 2] = v.z; rj[4 * g + 3] = v.w;
     }
   };
-  auto store_tile = [&](int buf) {
+  auto chain = [&](const bf16x8 (&kf)[8], const bf16x8 (&rf)[8]) -> f32x16 {
+    f32x16 acc;
 #pragma unroll
-    for (int m = 0; m < LPT; ++m) {
-      const int piece = t + m * NT;
-      const int row = piece >> 4, c16 = piece & 15;
-      if (piece < PIECES) *reinterpret_cast<uint4*>(kt[buf] + row * kLdsRowBytes + c16 * 16) = stage[m];
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], rf[kk], acc, 0, 0, 0);
+    return acc;
+  };
+  // K_i . u = sum of the three pseudo-key columns (accumulator elements 0..2 of lanes with half == 0)
+  {
+    bf16x8 pf[8];
+    read_k(pf, gram_lds, 0);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const f32x16 acc = chain(pf, res[rt]);
+      rowdot[rt] = (acc[2] + acc[1]) + acc[0];
+      asm volatile("" : "+v"(rowdot[rt]));       // settle the sum now; the accumulator is dead after this
     }
-    if (t < kTileCols) rjl[buf][t] = stage_r;
+  }
+
+  // Common-case test of one tile: max over the lane's 16 keys of acc * r_j (compare with T / r_i).
+  auto tile_max = [&](const f32x16& acc, const float (&rj)[16]) -> float {
+    float m = acc[0] * rj[0];
+#pragma unroll
+    for (int i = 1; i < 16; i += 3) m = fmaxf(m, fmaxf(acc[i] * rj[i], fmaxf(acc[i + 1] * rj[i + 1], acc[i + 2] * rj[i + 2])));
+    return m;
+  };
+  // Rare case: the row's hits in this tile, ranked by key (descending); forgive the first ones.
+  auto tile_hits = [&](const f32x16& acc, const float (&rj)[16], int rt, int c0) {
+    const int row = i0 + rt * 32 + lrow;
+    // Accumulator element i holds key c0 + 8*(i/4) + 4*half + i%4.  Masks are built with the bit
+    // positions of half 0 (compile-time constants) and shifted by 4*half once.
+    float tv[16];
+    uint32_t mine0 = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      tv[i] = acc[i] * rj[i];
+      if (tv[i] > thr[rt]) mine0 |= 1u << (8 * (i >> 2) + (i & 3));
+    }
+    uint32_t mine = mine0 << (4 * half);
+    const int self = row - c0;                                   // the diagonal, if it is in this tile
+    if (self >= 0 && self < 32) mine &= ~(1u << self);
+    const uint32_t all = mine | (uint32_t)__shfl_xor((int)mine, 32);
+    if (all != 0u) {
+      const int room = a.beta - cnt[rt];
+      uint32_t rem = all, sel = 0;
+      int taken = 0;
+      while (rem != 0u && taken < room) {
+        const uint32_t bit = 1u << (31 - __clz(rem));
+        sel |= bit;
+        rem &= ~bit;
+        ++taken;
+      }
+      const uint32_t take0 = (sel & mine) >> (4 * half);
+      float s = 0.f;
+#pragma unroll
+      for (int i = 15; i >= 0; --i) s += ((take0 >> (8 * (i >> 2) + (i & 3))) & 1u) ? tv[i] : 0.f;
+      s += __shfl_xor(s, 32);                    // both lanes of the row end with the same sum
+      sub[rt] += s;
+      cnt[rt] += taken;
+      if (cnt[rt] >= a.beta) thr[rt] = INFINITY;
+    }
+  };
+  // Scheduling hint for a block holding one 8-MFMA chain and one tile test (about 24 vector-ALU
+  // instructions): issue as 8 x (1 MFMA, 3 VALU) so the test runs in the shadow of the matrix pipe.
+  auto interleave = [&]() {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+    }
   };
 
-  if (nct > 0) {
-    load_tile(nct - 1);
-    store_tile(0);
-  }
-  __syncthreads();
-
+  // ---- stream the tiles, most recent first
   for (int it = 0; it < nct; ++it) {
     const int ct = nct - 1 - it;
     const int buf = it & 1;
-    if (it + 1 < nct) load_tile(ct - 1);
+    if (it + 1 < nct) issue_tile(ct - 1, buf ^ 1);
+    const unsigned char* tile = gram_lds + OFF_TILE + buf * TILE_SPAN;
+    const float* rjs = reinterpret_cast<const float*>(gram_lds + OFF_RJ + buf * TC * 4);
 
+    bf16x8 kf[2][8];
+    float rj[2][16];
+    f32x16 acc[2];
+    read_k(kf[(NS - 1) & 1], tile, NS - 1);
+    read_rj(rj[(NS - 1) & 1], rjs, NS - 1);
+    // software pipeline over the NS * RT tiles of this iteration: chain(q) with test(q - 1)
 #pragma unroll
-    for (int s = 1; s >= 0; --s) {
-      const int c0 = ct * kTileCols + s * 32;
-      bf16x8 bfr[8];
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk)
-        bfr[kk] = *reinterpret_cast<const bf16x8*>(kt[buf] + (s * 32 + lrow) * kLdsRowBytes + kk * 32 + half * 16);
-      const float rj = rjl[buf][s * 32 + lrow];
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt) {
-        f32x16 acc;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][kk], bfr[kk], acc, 0, 0, 0);
-        // common case: no unsaturated row of this tile has a partner above the threshold
-        float m = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < 16; i += 2)
-          m = fmaxf(m, fmaxf(fmaf(acc[i], rj, -thr[rt][i]), fmaf(acc[i + 1], rj, -thr[rt][i + 1])));
-        if (__any(m > 0.f)) {
-          // rare case: rank the hits of each row by column (descending) and forgive the first ones
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int rl = wave * 64 + rt * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-            const int row = rb * BM + rl;
-            const float tv = acc[i] * rj;
-            const bool hit = (tv > thr[rt][i]) && (row != c0 + lrow);
-            const unsigned long long mask = __ballot(hit);
-            if (mask != 0ull) {
-              const uint32_t hm = half ? (uint32_t)(mask >> 32) : (uint32_t)mask;
-              if (hm != 0u) {
-                const int c = cnt[rl];
-                const int room = a.beta - c;
-                const int ntake = min((int)__popc(hm), room);
-                uint32_t rem = hm;
-                float sacc = 0.f;
-                for (int z = 0; z < ntake; ++z) {
-                  const int src = 31 - __clz(rem);
-                  rem &= ~(1u << src);
-                  sacc += __shfl(tv, (lane & 32) | src);
-                }
-                // every lane of the half-wave holds the same values and stores them
-                sub[rl] = sub[rl] + sacc;
-                cnt[rl] = c + ntake;
-                if (c + ntake >= a.beta) thr[rt][i] = INFINITY;
-              }
-            }
-          }
-        }
+    for (int q2 = 0; q2 <= NS * RT; ++q2) {
+      if (q2 > 0) __builtin_amdgcn_sched_barrier(0);
+      if (q2 < NS * RT) {
+        const int s = NS - 1 - q2 / RT, rt = q2 % RT;
+        // prefetch the next subtile: its key fragments replace those of subtile s + 1 (all chains on
+        // them are issued); its r_j replace those of s + 1 one step later, after that subtile's last test
+        if (rt == 0 && s > 0) read_k(kf[(s - 1) & 1], tile, s - 1);
+        if (rt == 1 && s > 0) read_rj(rj[(s - 1) & 1], rjs, s - 1);
+        acc[q2 & 1] = chain(kf[s & 1], res[rt]);
+      }
+      if (q2 > 0) {
+        const int qp = q2 - 1;
+        const int sp = NS - 1 - qp / RT, rtp = qp % RT;
+        const float m = tile_max(acc[qp & 1], rj[sp & 1]);
+        if (q2 < NS * RT) interleave();
+        if (__any(m > thr[rtp])) tile_hits(acc[qp & 1], rj[sp & 1], rtp, ct * TC + sp * 32);
       }
     }
 
-    if (it + 1 < nct) store_tile(buf ^ 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
 
   // ---- closed-form row sums minus the forgiven similarities
-  for (int i = t; i < BM; i += NT) {
-    const int row = rb * BM + i;
-    if (row < n) {
-      const float r = rn[row];
-      const float self = 1.0f - a.eps * r;               // r_i |K_i| = 1 - eps r_i
-      const float total = r * rowdot[i] - self * self - r * sub[i];
-      a.sbar[(int64_t)head * a.n_pad + row] = total / (float)n;
+  if (half == 0) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int row = i0 + rt * 32 + lrow;
+      if (row < n) {
+        const float r = rn[row];
+        const float self = 1.0f - a.eps * r;               // r_i |K_i| = 1 - eps r_i
+        const float total = r * rowdot[rt] - self * self - r * sub[rt];
+        a.sbar[(int64_t)head * a.n_pad + row] = total / (float)n;
+      }
     }
   }
+}
+
+template <int NW, int RT, int TC>
+hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
+  constexpr int BM = NW * RT * 32;
+  constexpr size_t lds = kPseudoBytes + 2 * (size_t)TC * kRowBytes + 2 * (size_t)TC * 4;
+  static bool configured = false;
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  a.row_blocks = (pl.n + BM - 1) / BM;
+  const int head_groups = (pl.heads + 7) / 8;
+  const dim3 grid((unsigned)((int64_t)head_groups * a.row_blocks * 8));
+  hipLaunchKernelGGL((gram_kernel<NW, RT, TC>), grid, dim3(NW * 64), lds, stream, a);
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -229,18 +316,8 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.H = pl.H; a.heads = pl.heads; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks; a.beta = pl.beta;
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   a.T = pl.T; a.eps = pl.eps;
-  // rows per workgroup: 256 unless 192 wastes fewer padded rows
-  const int rb4 = (pl.n + 255) / 256, rb3 = (pl.n + 191) / 192;
-  const bool use3 = rb3 * 192 < rb4 * 256;
-  a.row_blocks = use3 ? rb3 : rb4;
-  const int head_groups = (pl.heads + 7) / 8;
-  const dim3 grid((unsigned)((int64_t)head_groups * a.row_blocks * 8));
-  if (use3) {
-    hipLaunchKernelGGL((gram_kernel<3>), grid, dim3(192), 0, stream, a);
-  } else {
-    hipLaunchKernelGGL((gram_kernel<4>), grid, dim3(256), 0, stream, a);
-  }
-  return hipGetLastError();
+  a.row_blocks = 0;
+  return launch_shape<4, 2, 128>(a, pl, stream);
 }
 
 }  // namespace rkv
