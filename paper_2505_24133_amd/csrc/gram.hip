@@ -18,6 +18,8 @@
 // the 16-byte fragment reads hit without bank conflicts.  Per 32x32 tile the common-case
 // epilogue is one multiply per element folded into a running max, issued in the shadow of the
 // next tile's MFMA chain; K_i . u comes from three extra pseudo-keys (u split into bf16 pieces).
+#include <type_traits>
+
 #include "rkv_internal.h"
 
 namespace rkv {
@@ -45,22 +47,24 @@ __device__ __forceinline__ int slot_offset(int row, int chunk) { return row * kR
 // One wave-wide DMA copy: lane l fetches 16 bytes at base + voff and the hardware stores them
 // at LDS address lds_base + 16 * l.  Issued as inline assembly so that the compiler does not
 // serialise later LDS reads of the *other* buffer behind it; completion is awaited explicitly
-// (vmcnt) before the barrier that publishes the buffer.
+// (vmcnt) before the barrier that publishes the buffer.  M0 is written here; the compiler keeps no
+// value in M0 across statements on this target (it sets M0 immediately before each of its own uses).
 __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_base), "v"(voff), "s"(base)
-               : "memory", "m0");
+               : "memory");
 }
 __device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2"
                :
                : "s"(lds_base), "v"(voff), "s"(base)
-               : "memory", "m0");
+               : "memory");
 }
 
 template <int NW, int RT, int TC>
 __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
+  constexpr int NT = NW * 64;
   constexpr int BM = NW * RT * 32;
   constexpr int NS = TC / 32;                       // 32-key subtiles per tile
   constexpr int LOADS = TC / 4;                     // wave-wide DMA copies per tile (4 rows each)
@@ -92,40 +96,63 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
   const float* rn = a.rnorm + (int64_t)head * a.n_pad;
   const int n = a.n;
   const int i0 = rb * BM + wave * (RT * 32);
-  const uint32_t lds0 = (uint32_t)(uintptr_t)gram_lds;   // LDS byte address of the dynamic segment
+  const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)gram_lds);   // LDS byte address of the dynamic segment
   const uint32_t row_bytes = (uint32_t)a.kst * 2u;
 
   // Copy tile `ct` (keys ct*TC ...) and its r_j into buffer `buf`.  Keys past n are read from
   // row n-1 (any finite row will do: their r_j is 0).
-  auto issue_tile = [&](int ct, int buf) {
-    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + OFF_TILE + buf * TILE_SPAN + wave * 1024);
-#pragma unroll
-    for (int jj = 0; jj < LOADS / NW; ++jj) {
-      const int row = (wave + jj * NW) * 4 + (lane >> 4);     // row inside the tile
-      const int key = min(ct * TC + row, n - 1);
-      const int chunk = (lane & 15) ^ (row & 15);            // the chunk that belongs in this lane's slot
-      dma16(kbase, (uint32_t)key * row_bytes + (uint32_t)chunk * 16u, dst + jj * NW * 1024);
+  // One wave-wide DMA copy (4 rows) of tile `ct` into buffer `buf`; each wave issues LOADS / NW of them.
+  // Only the last tile can reach past n (CLAMP); for the others the row part of the address is
+  // wave-uniform and goes into the scalar base, leaving one per-lane offset register.
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  auto issue_rows = [&](int ct, int buf, int jj, auto clamp) {
+    const int row0 = (wave_s + jj * NW) * 4;                   // first of the 4 rows, inside the tile
+    const uint32_t dst = lds0 + OFF_TILE + buf * TILE_SPAN + row0 * kRowBytes;
+    const int chunk = (lane & 15) ^ ((row0 + (lane >> 4)) & 15);   // the chunk that belongs in this lane's slot
+    if constexpr (decltype(clamp)::value) {
+      const int key = min(ct * TC + row0 + (lane >> 4), n - 1);
+      dma16(kbase, (uint32_t)key * row_bytes + (uint32_t)chunk * 16u, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
+    } else {
+      const uint64_t addr = (uint64_t)(uintptr_t)kbase + (uint64_t)(uint32_t)(ct * TC + row0) * row_bytes;
+      // wave-uniform by construction; readfirstlane returns a signed int, so each half is narrowed to
+      // uint32_t before widening (a sign-extended low half would overwrite the high half)
+      const uint32_t addr_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(addr >> 32));
+      const uint32_t addr_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
+      const uint64_t addr_s = ((uint64_t)addr_hi << 32) | (uint64_t)addr_lo;
+      dma16(reinterpret_cast<const void*>(addr_s), (uint32_t)(lane >> 4) * row_bytes + (uint32_t)chunk * 16u,
+            (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
     }
+  };
+  auto issue_rj = [&](int ct, int buf) {
     if (wave < TC / 64)
       dma4(rn + ct * TC, (uint32_t)(wave * 64 + lane) * 4u,
            __builtin_amdgcn_readfirstlane(lds0 + OFF_RJ + buf * TC * 4 + wave * 256));
+  };
+  auto issue_tile = [&](int ct, int buf) {
+#pragma unroll
+    for (int jj = 0; jj < LOADS / NW; ++jj) issue_rows(ct, buf, jj, std::true_type{});
+    issue_rj(ct, buf);
   };
   const int nct = (a.beta > 0) ? (n + TC - 1) / TC : 0;
   if (nct > 0) issue_tile(nct - 1, 0);
 
   // ---- prologue: u -> three bf16 pseudo-keys, the wave's rows -> registers
-  if (t < kHeadDim) {
-    const float* up = a.upart + (int64_t)head * a.chunks * kHeadDim + t;
-    float u = 0.f;
-    for (int c = 0; c < a.chunks; ++c) u += up[(int64_t)c * kHeadDim];
-#pragma unroll
-    for (int piece = 0; piece < 3; ++piece) {
-      uint32_t bits = __float_as_uint(u);
-      bits += 0x7fffu + ((bits >> 16) & 1u);                  // round to nearest even bf16
-      const uint16_t hb = (uint16_t)(bits >> 16);
-      u -= __uint_as_float((uint32_t)hb << 16);               // exact remainder
-      *reinterpret_cast<uint16_t*>(gram_lds + slot_offset(piece, t >> 3) + (t & 7) * 2) = hb;
+  {
+    // u = sum of the pre-pass's per-chunk partials, in a fixed order; all threads load in parallel
+    constexpr int GROUPS = NT / kHeadDim;
+    float* ured = reinterpret_cast<float*>(gram_lds + OFF_TILE + TILE_SPAN);   // tile 1 is not in use yet
+    const int e = t & (kHeadDim - 1), grp = t >> 7;
+    const float* up = a.upart + (int64_t)head * a.chunks * kHeadDim + e;
+    float u0 = 0.f, u1 = 0.f, u2 = 0.f, u3 = 0.f;
+    int c = grp;
+    for (; c + 3 * GROUPS < a.chunks; c += 4 * GROUPS) {
+      u0 += up[(int64_t)c * kHeadDim];
+      u1 += up[(int64_t)(c + GROUPS) * kHeadDim];
+      u2 += up[(int64_t)(c + 2 * GROUPS) * kHeadDim];
+      u3 += up[(int64_t)(c + 3 * GROUPS) * kHeadDim];
     }
+    for (; c < a.chunks; c += GROUPS) u0 += up[(int64_t)c * kHeadDim];
+    ured[t] = (u0 + u1) + (u2 + u3);
   }
   bf16x8 res[RT][8];
   float thr[RT], sub[RT], rowdot[RT];
@@ -142,6 +169,22 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
     thr[rt] = (row < n && a.beta > 0) ? a.T / rn[row] : INFINITY;
     sub[rt] = 0.f;
     cnt[rt] = 0;
+  }
+  __syncthreads();
+  if (t < kHeadDim) {
+    constexpr int GROUPS = NT / kHeadDim;
+    const float* ured = reinterpret_cast<const float*>(gram_lds + OFF_TILE + TILE_SPAN);
+    float u = ured[t];
+#pragma unroll
+    for (int g = 1; g < GROUPS; ++g) u += ured[t + g * kHeadDim];
+#pragma unroll
+    for (int piece = 0; piece < 3; ++piece) {
+      uint32_t bits = __float_as_uint(u);
+      bits += 0x7fffu + ((bits >> 16) & 1u);                  // round to nearest even bf16
+      const uint16_t hb = (uint16_t)(bits >> 16);
+      u -= __uint_as_float((uint32_t)hb << 16);               // exact remainder
+      *reinterpret_cast<uint16_t*>(gram_lds + slot_offset(piece, t >> 3) + (t & 7) * 2) = hb;
+    }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
@@ -238,7 +281,8 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
   for (int it = 0; it < nct; ++it) {
     const int ct = nct - 1 - it;
     const int buf = it & 1;
-    if (it + 1 < nct) issue_tile(ct - 1, buf ^ 1);
+    const bool more = it + 1 < nct;
+    if (more) issue_rj(ct - 1, buf ^ 1);
     const unsigned char* tile = gram_lds + OFF_TILE + buf * TILE_SPAN;
     const float* rjs = reinterpret_cast<const float*>(gram_lds + OFF_RJ + buf * TC * 4);
 
@@ -258,6 +302,11 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
         if (rt == 0 && s > 0) read_k(kf[(s - 1) & 1], tile, s - 1);
         if (rt == 1 && s > 0) read_rj(rj[(s - 1) & 1], rjs, s - 1);
         acc[q2 & 1] = chain(kf[s & 1], res[rt]);
+        // the next tile's DMA copies are spread over the steps instead of stalling the wave up front
+        constexpr int PER_STEP = (LOADS / NW + NS * RT - 1) / (NS * RT);
+#pragma unroll
+        for (int d = 0; d < PER_STEP; ++d)
+          if (more && q2 * PER_STEP + d < LOADS / NW) issue_rows(ct - 1, buf ^ 1, q2 * PER_STEP + d, std::false_type{});
       }
       if (q2 > 0) {
         const int qp = q2 - 1;
