@@ -71,6 +71,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sim-threshold", type=float, default=None)
     ap.add_argument("--beta", type=int, default=None)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (heads shard across GPUs with no exchange; "
@@ -142,6 +144,13 @@ def main() -> int:
     for i in range(5 * K):
         hip.hipEventDestroy(handles[i])
     avg = stage_ms.mean(axis=0)
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     # ---- algorithmic work of one launch (one step)
     heads = w.num_problems * w.kv_heads
