@@ -6,6 +6,8 @@
 //                select on order-preserving integer keys held in LDS, ties resolved towards the
 //                larger index, kept indices emitted in ascending order by a workgroup prefix scan,
 //                followed by the alpha observation rows (Sec. 3.1).
+#include <algorithm>
+
 #include "rkv_internal.h"
 
 namespace rkv {
@@ -14,6 +16,7 @@ namespace {
 
 constexpr int kFinThreads = 1024;
 constexpr int kFinWaves = kFinThreads / 64;
+constexpr int kMaxPoolFloats = 16384;           // 64 KB of LDS for the pooling stage
 
 struct FinArgs {
   const float* logit;    // [heads][alpha][n_pad]
@@ -22,11 +25,12 @@ struct FinArgs {
   const float* imp_in;   // [heads][n] (select-only mode)
   const float* red_in;   // [heads][n]
   float* imp_out;        // [heads][n] or nullptr
+  float* imp_tmp;        // [heads][n_pad] scratch for the fused path
   float* red_out;        // [heads][n] or nullptr
   float* sbar_out;       // [heads][n] or nullptr
   float* score_out;      // [heads][n] or nullptr
   int32_t* kept;         // [heads][budget]
-  int n, n_pad, chunks, alpha, W, k_sel, budget;
+  int n, n_pad, chunks, alpha, W, k_sel, budget, pool_floats;
   float lambda;
 };
 
@@ -88,7 +92,7 @@ __device__ __forceinline__ uint32_t order_key(float z) {
 
 template <int MODE>
 __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
-  extern __shared__ uint32_t keys[];            // n_pad order-preserving keys (select mode)
+  extern __shared__ uint32_t keys[];            // n_pad order-preserving keys (select mode) / pooling stage
   __shared__ float red[kFinWaves];
   __shared__ uint32_t scan_buf[kFinWaves];
   __shared__ float gmax[kMaxQRows], ginv[kMaxQRows];
@@ -102,17 +106,21 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   const float* lg = a.logit + (int64_t)head * a.alpha * a.n_pad;
   const float* sb = a.sbar + (int64_t)head * a.n_pad;
 
-  // ---- softmax denominators
+  // ---- softmax denominators: one wave per query row, lanes over the chunks
   if constexpr ((MODE & kModeImportance) != 0) {
-    if (t < a.alpha) {
-      const float* st = a.stats + ((int64_t)head * a.chunks * a.alpha + t) * 2;
+    for (int j = t >> 6; j < a.alpha; j += kFinWaves) {
+      const float* st = a.stats + ((int64_t)head * a.chunks * a.alpha + j) * 2;
       float m = -INFINITY;
-      for (int c = 0; c < a.chunks; ++c) m = fmaxf(m, st[(int64_t)c * a.alpha * 2]);
+      for (int c = lane; c < a.chunks; c += 64) m = fmaxf(m, st[(int64_t)c * a.alpha * 2]);
+      m = wave_max(m);
       float den = 0.f;
-      for (int c = 0; c < a.chunks; ++c)
+      for (int c = lane; c < a.chunks; c += 64)
         den += st[(int64_t)c * a.alpha * 2 + 1] * expf(st[(int64_t)c * a.alpha * 2] - m);
-      gmax[t] = m;
-      ginv[t] = 1.0f / (den * (float)a.alpha);
+      den = wave_sum(den);
+      if (lane == 0) {
+        gmax[j] = m;
+        ginv[j] = 1.0f / (den * (float)a.alpha);
+      }
     }
   }
   float smax = 0.f, sinv = 0.f;
@@ -126,21 +134,47 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   }
   __syncthreads();
 
-  // ---- per-candidate scores
-  for (int i = t; i < n; i += kFinThreads) {
-    float imp = 0.f, rd = 0.f;
-    if constexpr ((MODE & kModeImportance) != 0) {
-      const int lo = (a.W > 0) ? max(0, i - a.W) : i;
-      const int hi = (a.W > 0) ? min(n - 1, i + a.W - 1) : i;
+  // ---- importance: the group-max logits are staged in LDS a block of columns at a time (with a halo
+  // of W columns, -inf outside [0, n)), so the 2W x alpha window reads per candidate are LDS reads
+  float* imp_dst = nullptr;
+  if constexpr ((MODE & kModeImportance) != 0) {
+    imp_dst = a.imp_out ? a.imp_out + (int64_t)head * n : a.imp_tmp + (int64_t)head * a.n_pad;
+    float* pool = reinterpret_cast<float*>(keys);            // the key buffer is not in use yet
+    const int win = (a.W > 0) ? 2 * a.W : 1;
+    const int halo = win - 1;
+    const int block_cols = a.pool_floats / a.alpha - halo;    // >= 1 (checked on the host)
+    for (int cb = 0; cb < n; cb += block_cols) {
+      const int cols = min(block_cols, n - cb);
+      const int width = cols + halo;
+      const int first = cb - a.W;                              // column held at pool[j][0]
       for (int j = 0; j < a.alpha; ++j) {
         const float* row = lg + (int64_t)j * a.n_pad;
-        float m = row[lo];
-        for (int c = lo + 1; c <= hi; ++c) m = fmaxf(m, row[c]);
-        imp += expf(m - gmax[j]) * ginv[j];
+        for (int c = t; c < width; c += kFinThreads) {
+          const int col = first + c;
+          pool[j * width + c] = (col >= 0 && col < n) ? row[col] : -INFINITY;
+        }
       }
-      if (a.imp_out) a.imp_out[(int64_t)head * n + i] = imp;
-    } else if constexpr ((MODE & kModeSelect) != 0) {
-      imp = a.imp_in[(int64_t)head * n + i];
+      __syncthreads();
+      for (int li = t; li < cols; li += kFinThreads) {
+        float imp = 0.f;
+        for (int j = 0; j < a.alpha; ++j) {
+          const float* wrow = pool + j * width + li;          // window [i - W, i + W - 1] starts here
+          float m = wrow[0];
+          for (int c = 1; c < win; ++c) m = fmaxf(m, wrow[c]);
+          imp += expf(m - gmax[j]) * ginv[j];
+        }
+        imp_dst[cb + li] = imp;
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- per-candidate redundancy and joint score
+  for (int i = t; i < n; i += kFinThreads) {
+    float imp = 0.f, rd = 0.f;
+    if constexpr ((MODE & kModeSelect) != 0) {
+      if constexpr ((MODE & kModeImportance) != 0) imp = imp_dst[i];
+      else imp = a.imp_in[(int64_t)head * n + i];
     }
     if constexpr ((MODE & kModeRedundancy) != 0) {
       const float s = sb[i];
@@ -224,6 +258,13 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
 
 template <int MODE>
 hipError_t launch_mode(const FinArgs& a, int heads, size_t lds, hipStream_t stream) {
+  static bool configured = false;
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&finalize_kernel<MODE>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
   hipLaunchKernelGGL((finalize_kernel<MODE>), dim3(heads), dim3(kFinThreads), lds, stream, a);
   return hipGetLastError();
 }
@@ -244,7 +285,20 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks; a.alpha = pl.alpha; a.W = pl.W;
   a.k_sel = pl.k_sel; a.budget = pl.budget;
   a.lambda = pl.lambda;
-  const size_t lds = (mode & kModeSelect) ? (size_t)pl.n_pad * sizeof(uint32_t) : 0;
+  a.imp_tmp = reinterpret_cast<float*>(ws + pl.off_imp);
+  // dynamic LDS: the select keys (n_pad words) and the pooling stage share one region
+  size_t words = (mode & kModeSelect) ? (size_t)pl.n_pad : 0;
+  a.pool_floats = 0;
+  if (mode & kModeImportance) {
+    const int win = pl.W > 0 ? 2 * pl.W : 1;
+    const size_t want = (size_t)pl.alpha * (size_t)(std::min(pl.n, 2048) + win - 1);
+    const size_t least = (size_t)pl.alpha * (size_t)win;          // one column per block at the very least
+    size_t pool = std::min(std::max(want, least), (size_t)kMaxPoolFloats);
+    if (pool < least) return hipErrorInvalidValue;                // rejected earlier by make_plan
+    a.pool_floats = (int)pool;
+    words = std::max(words, pool);
+  }
+  const size_t lds = words * sizeof(uint32_t);
   switch (mode) {
     case kModeImportance: return launch_mode<kModeImportance>(a, pl.heads, lds, stream);
     case kModeRedundancy: return launch_mode<kModeRedundancy>(a, pl.heads, lds, stream);

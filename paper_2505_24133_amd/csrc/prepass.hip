@@ -29,9 +29,12 @@ struct PrepassArgs {
 
 template <bool HAS_Q, int MT>
 __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a) {
+  // The logit tile reuses the key tile's LDS once every wave has read its key fragments
+  // (MT * 32 rows x 136 floats <= 128 rows x 272 bytes), which lets four workgroups share a CU.
   __shared__ __attribute__((aligned(16))) unsigned char ks[kChunk * kLdsRowBytes];
   __shared__ float ured[4][kHeadDim];
-  __shared__ float lg[HAS_Q ? MT * 32 : 1][kLogitStride];
+  float (*lg)[kLogitStride] = reinterpret_cast<float (*)[kLogitStride]>(ks);
+  static_assert(2 * 32 * kLogitStride * sizeof(float) <= sizeof(ks), "logit tile must fit in the key tile");
 
   const int t = threadIdx.x;
   const int lane = t & 63;
@@ -120,6 +123,7 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf, acc[mt], 0, 0, 0);
       }
     }
+    __syncthreads();      // all key fragments are in registers: the tile can be overwritten
     // accumulator layout: column (key) = lane % 32, row (query) = 8*(i/4) + 4*(lane/32) + i%4
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
