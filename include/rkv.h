@@ -48,7 +48,7 @@ typedef enum {
 } rkv_status;
 
 typedef struct {
-  int32_t num_problems;      /* P >= 1 */
+  int32_t num_problems;      /* P >= 0; an empty batch is valid and enqueues nothing */
   int32_t kv_heads;          /* H */
   int32_t q_heads;           /* H * G */
   int32_t n_tokens;          /* N = rows currently held per head (budget + buffer) */

@@ -11,7 +11,7 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   if (prm == nullptr) return RKV_ERR_NULL;
   const rkv_params& q = *prm;
-  if (q.num_problems < 1 || q.kv_heads < 1 || q.q_heads < 1 || q.alpha < 1 || q.n_tokens < 1 || q.budget < 1)
+  if (q.num_problems < 0 || q.kv_heads < 1 || q.q_heads < 1 || q.alpha < 1 || q.n_tokens < 1 || q.budget < 1)
     return RKV_ERR_SHAPE;
   if (q.q_heads % q.kv_heads != 0) return RKV_ERR_SHAPE;
   if (q.n_tokens <= q.alpha || q.budget <= q.alpha) return RKV_ERR_SHAPE;
@@ -62,11 +62,15 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
 }
 
 static rkv_status check_ws(const Plan& pl, const void* ws, size_t ws_bytes) {
+  if (pl.total == 0) return RKV_OK;     // empty batch: no scratch needed
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || ws_bytes < pl.total) return RKV_ERR_WORKSPACE;
   return RKV_OK;
 }
 
 static rkv_status hip_status(hipError_t e) { return e == hipSuccess ? RKV_OK : RKV_ERR_HIP; }
+
+// An empty batch (num_problems == 0) is valid and enqueues nothing.
+static bool empty(const Plan& pl) { return pl.heads == 0; }
 
 }  // namespace rkv
 
@@ -85,10 +89,11 @@ rkv_status rkv_workspace_size(const rkv_params* prm, size_t* bytes) {
 
 rkv_status rkv_score_importance(const rkv_params* prm, const void* q_obs, const void* k,
                                 float* importance, void* ws, size_t ws_bytes, void* stream) {
-  if (q_obs == nullptr || k == nullptr || importance == nullptr) return RKV_ERR_NULL;
   Plan pl;
   rkv_status s = make_plan(prm, &pl);
   if (s != RKV_OK) return s;
+  if (empty(pl)) return RKV_OK;
+  if (q_obs == nullptr || k == nullptr || importance == nullptr) return RKV_ERR_NULL;
   if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* w = static_cast<char*>(ws);
@@ -99,10 +104,11 @@ rkv_status rkv_score_importance(const rkv_params* prm, const void* q_obs, const 
 
 rkv_status rkv_score_redundancy(const rkv_params* prm, const void* k, float* redundancy,
                                 float* mean_sim, void* ws, size_t ws_bytes, void* stream) {
-  if (k == nullptr || redundancy == nullptr) return RKV_ERR_NULL;
   Plan pl;
   rkv_status s = make_plan(prm, &pl);
   if (s != RKV_OK) return s;
+  if (empty(pl)) return RKV_OK;
+  if (k == nullptr || redundancy == nullptr) return RKV_ERR_NULL;
   if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* w = static_cast<char*>(ws);
@@ -114,10 +120,11 @@ rkv_status rkv_score_redundancy(const rkv_params* prm, const void* k, float* red
 
 rkv_status rkv_select_topk(const rkv_params* prm, const float* importance, const float* redundancy,
                            float* score, int32_t* kept_idx, void* ws, size_t ws_bytes, void* stream) {
-  if (importance == nullptr || redundancy == nullptr || kept_idx == nullptr) return RKV_ERR_NULL;
   Plan pl;
   rkv_status s = make_plan(prm, &pl);
   if (s != RKV_OK) return s;
+  if (empty(pl)) return RKV_OK;
+  if (importance == nullptr || redundancy == nullptr || kept_idx == nullptr) return RKV_ERR_NULL;
   if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
   if (pl.N <= pl.budget) return RKV_NOT_TRIGGERED;
   return hip_status(launch_finalize(pl, kModeSelect, static_cast<char*>(ws), importance, redundancy, nullptr,
@@ -126,20 +133,22 @@ rkv_status rkv_select_topk(const rkv_params* prm, const float* importance, const
 
 rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, const int32_t* kept_idx,
                        void* k_out, void* v_out, void* stream) {
-  if (k == nullptr || v == nullptr || kept_idx == nullptr || k_out == nullptr || v_out == nullptr) return RKV_ERR_NULL;
   Plan pl;
   const rkv_status s = make_plan(prm, &pl);
   if (s != RKV_OK) return s;
+  if (empty(pl)) return RKV_OK;
+  if (k == nullptr || v == nullptr || kept_idx == nullptr || k_out == nullptr || v_out == nullptr) return RKV_ERR_NULL;
   return hip_status(launch_gather(pl, k, v, kept_idx, k_out, v_out, static_cast<hipStream_t>(stream)));
 }
 
 static rkv_status compress_impl(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
                                 void* k_out, void* v_out, int32_t* kept_idx, float* score,
                                 void* ws, size_t ws_bytes, void* stream, void* const* events) {
-  if (q_obs == nullptr || k == nullptr || v == nullptr || k_out == nullptr || v_out == nullptr) return RKV_ERR_NULL;
   Plan pl;
   rkv_status s = make_plan(prm, &pl);
   if (s != RKV_OK) return s;
+  if (empty(pl)) return RKV_OK;
+  if (q_obs == nullptr || k == nullptr || v == nullptr || k_out == nullptr || v_out == nullptr) return RKV_ERR_NULL;
   if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
   if (pl.N <= pl.budget) return RKV_NOT_TRIGGERED;
   hipStream_t st = static_cast<hipStream_t>(stream);

@@ -6,6 +6,8 @@
 //     fp32 accumulation) and the chunk's (max, sum exp) per query row for the softmax over
 //     all candidates, which the finalize kernel completes.
 // HBM-bound: every key byte is read exactly once, coalesced, and staged in LDS.
+#include <algorithm>
+
 #include "rkv_internal.h"
 
 namespace rkv {
@@ -15,6 +17,15 @@ namespace {
 constexpr int kPrepassThreads = 256;
 constexpr int kLogitStride = kChunk + 8;   // floats; +8 puts the two half-waves on disjoint banks
 
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+// v + (v of the lane selected by the DPP control), within rows of 16 lanes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return v + __int_as_float(x);
+}
+
 struct PrepassArgs {
   const uint16_t* q;      // [P, Hq, alpha, d] or nullptr
   const uint16_t* k;
@@ -22,7 +33,7 @@ struct PrepassArgs {
   float* upart;
   float* logit;
   float* stats;
-  int H, G, alpha, n, n_pad, chunks;
+  int H, G, alpha, n, n_pad, chunks, items;
   int64_t ksp, ksh, kst;
   float eps, scale;
 };
@@ -39,26 +50,39 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wave = t >> 6;
-  const int head = blockIdx.x / a.chunks;
-  const int chunk = blockIdx.x - head * a.chunks;
+  const int c16 = t & 15;
+  const int rbase = t >> 4;
+
+  // Persistent workgroups: each walks over (head, chunk) items and fetches the next item's keys
+  // into registers while it works on the current one, so HBM requests are always in flight.
+  auto fetch = [&](int item, uint4 (&dst)[8]) {
+    const int hd = item / a.chunks;
+    const int ck = item - hd * a.chunks;
+    const int pp = hd / a.H;
+    const uint16_t* kb = a.k + pp * a.ksp + (hd - pp * a.H) * a.ksh;
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const int grow = ck * kChunk + m * 16 + rbase;
+      dst[m] = make_uint4(0, 0, 0, 0);
+      if (grow < a.n) dst[m] = *reinterpret_cast<const uint4*>(kb + (int64_t)grow * a.kst + c16 * 8);
+    }
+  };
+  uint4 regs[8], next[8];
+  if ((int)blockIdx.x < a.items) fetch(blockIdx.x, regs);
+
+  for (int item = blockIdx.x; item < a.items; item += gridDim.x) {
+  const int head = item / a.chunks;
+  const int chunk = item - head * a.chunks;
   const int p = head / a.H;
   const int h = head - p * a.H;
   const int j0 = chunk * kChunk;
-  const uint16_t* kbase = a.k + p * a.ksp + h * a.ksh;
+  const bool has_next = item + (int)gridDim.x < a.items;
+  if (has_next) fetch(item + gridDim.x, next);
 
-  // ---- stage the chunk in LDS (coalesced 16-byte loads), norms and the chunk's share of u
-  const int c16 = t & 15;
-  const int rbase = t >> 4;
+  // ---- stage the chunk in LDS, norms and the chunk's share of u
   float uacc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) uacc[e] = 0.f;
-  uint4 regs[8];
-#pragma unroll
-  for (int m = 0; m < 8; ++m) {
-    const int grow = j0 + m * 16 + rbase;
-    regs[m] = make_uint4(0, 0, 0, 0);
-    if (grow < a.n) regs[m] = *reinterpret_cast<const uint4*>(kbase + (int64_t)grow * a.kst + c16 * 8);
-  }
 #pragma unroll
   for (int m = 0; m < 8; ++m) {
     const int row = m * 16 + rbase;
@@ -72,14 +96,21 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
       f[2 * e] = __uint_as_float(w4[e] << 16);
       f[2 * e + 1] = __uint_as_float(w4[e] & 0xffff0000u);
     }
+    // |K_row|^2: packed bf16 dot products, then a butterfly over the 16 lanes that share the row
     float ss = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) ss = fmaf(f[e], f[e], ss);
-    ss += __shfl_xor(ss, 1);
-    ss += __shfl_xor(ss, 2);
-    ss += __shfl_xor(ss, 4);
-    ss += __shfl_xor(ss, 8);
-    const float r = (grow < a.n) ? 1.0f / (sqrtf(ss) + a.eps) : 0.f;
+    for (int e = 0; e < 4; ++e) {
+      bf16x2 pr;
+      __builtin_memcpy(&pr, &w4[e], 4);
+      ss = __builtin_amdgcn_fdot2_f32_bf16(pr, pr, ss, false);
+    }
+    ss = dpp_add<0xB1>(ss);     // quad_perm [1,0,3,2]
+    ss = dpp_add<0x4E>(ss);     // quad_perm [2,3,0,1]
+    ss = dpp_add<0x141>(ss);    // row_half_mirror
+    ss = dpp_add<0x140>(ss);    // row_mirror
+    // hardware sqrt / reciprocal (1 ulp each): r enters every score only through products that are
+    // compared at 1e-3 relative, and the threshold test tolerates 1e-5 absolute
+    const float r = (grow < a.n) ? __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(ss) + a.eps) : 0.f;
     if (c16 == 0) a.rnorm[(int64_t)head * a.n_pad + grow] = r;
 #pragma unroll
     for (int e = 0; e < 8; ++e) uacc[e] = fmaf(r, f[e], uacc[e]);
@@ -161,6 +192,12 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
       }
     }
   }
+  __syncthreads();          // the tiles are rewritten by the next item
+  if (has_next) {
+#pragma unroll
+    for (int m = 0; m < 8; ++m) regs[m] = next[m];
+  }
+  }  // items
 }
 
 }  // namespace
@@ -177,7 +214,19 @@ hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   a.eps = pl.eps;
   a.scale = 1.0f / sqrtf((float)kHeadDim);
-  const dim3 grid((unsigned)((int64_t)pl.heads * pl.chunks)), block(kPrepassThreads);
+  a.items = pl.heads * pl.chunks;
+  // as many workgroups as stay resident at once (queried once per kernel variant)
+  auto resident = [](const void* fn) {
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kPrepassThreads, 0) != hipSuccess || per_cu < 1) per_cu = 2;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    return per_cu * cus;
+  };
+  static const int res_noq = resident(reinterpret_cast<const void*>(&prepass_kernel<false, 1>));
+  static const int res_q1 = resident(reinterpret_cast<const void*>(&prepass_kernel<true, 1>));
+  static const int res_q2 = resident(reinterpret_cast<const void*>(&prepass_kernel<true, 2>));
+  const int res = (q_obs == nullptr) ? res_noq : (pl.G * pl.alpha <= 32 ? res_q1 : res_q2);
+  const dim3 grid((unsigned)std::min(a.items, res)), block(kPrepassThreads);
   if (q_obs == nullptr) {
     hipLaunchKernelGGL((prepass_kernel<false, 1>), grid, block, 0, stream, a);
   } else if (pl.G * pl.alpha <= 32) {

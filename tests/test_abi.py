@@ -54,6 +54,9 @@ def test_workspace_size_and_validation(lib):
     assert st == rkv.RKV_OK and nbytes > 0 and nbytes % 256 == 0
     st2, nbytes2 = ws_status(lib, shape(num_problems=4))
     assert st2 == rkv.RKV_OK and nbytes2 > nbytes
+    assert ws_status(lib, shape(num_problems=0)) == (rkv.RKV_OK, 0)
+    assert ws_status(lib, shape(num_problems=-1))[0] == rkv.RKV_ERR_SHAPE
+    assert ws_status(lib, shape(pool_w=1025, alpha=8))[0] == rkv.RKV_ERR_UNSUPPORTED
     assert ws_status(lib, shape(q_heads=30))[0] == rkv.RKV_ERR_SHAPE
     assert ws_status(lib, shape(budget=8))[0] == rkv.RKV_ERR_SHAPE
     assert ws_status(lib, shape(n_tokens=8))[0] == rkv.RKV_ERR_SHAPE

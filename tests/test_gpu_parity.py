@@ -317,3 +317,56 @@ def test_not_triggered_leaves_outputs_untouched():
     torch.cuda.synchronize()
     assert st == rkv.RKV_NOT_TRIGGERED
     assert bool((ko == 7.0).all()) and bool((vo == 7.0).all())
+
+
+# ------------------------------------------------------------------------- degenerate inputs
+def _custom(kf, qf, vf, **kw):
+    """float32 arrays [P,H,N,d], [P,Hq,alpha,d] -> workload + bf16 bit arrays."""
+    P, H, N, d = kf.shape
+    w = synth.Workload("custom", P, H, qf.shape[1], N, kw.pop("budget"), alpha=qf.shape[2], **kw)
+    return w, synth.f32_to_bf16_bits(qf), synth.f32_to_bf16_bits(kf), synth.f32_to_bf16_bits(vf)
+
+
+def test_smallest_problem():
+    """n = 2 candidates, k = 1 selected."""
+    rng = np.random.default_rng(21)
+    kf = rng.standard_normal((3, 2, 10, 128)).astype(np.float32)
+    qf = rng.standard_normal((3, 8, 8, 128)).astype(np.float32)
+    w, q, k, v = _custom(kf, qf, kf[::-1].copy(), budget=9, pool_w=4, beta=1, sim_threshold=0.5, lam=0.1)
+    run_fused(w, q, k, v, [(p, h) for p in range(3) for h in range(2)], "tiny", check_parts=True)
+
+
+def test_all_keys_identical():
+    """Every pair is a hit (S = 1 up to eps); beta = 2 forgives the two most recent partners of each row."""
+    rng = np.random.default_rng(22)
+    row = rng.standard_normal(128).astype(np.float32)
+    kf = np.tile(row, (1, 1, 300, 1)).astype(np.float32)
+    qf = rng.standard_normal((1, 4, 8, 128)).astype(np.float32)
+    vf = rng.standard_normal((1, 1, 300, 128)).astype(np.float32)
+    w, q, k, v = _custom(kf, qf, vf, budget=200, pool_w=2, beta=2, sim_threshold=0.9, lam=0.0)
+    idx, score, ko, vo = run_fused(w, q, k, v, [(0, 0)], "identical", check_parts=True)
+    # all scores equal -> the most recent candidates are kept
+    np.testing.assert_array_equal(idx[0, 0].cpu().numpy(), np.arange(100, 300))
+
+
+def test_zero_rows_and_large_magnitudes():
+    rng = np.random.default_rng(23)
+    kf = rng.standard_normal((1, 2, 260, 128)).astype(np.float32)
+    kf[0, 0, [0, 17, 100, 251]] = 0.0                 # zero keys: similarity 0 to everything (eps keeps it finite)
+    kf[0, 1, 40:60] *= 3.0e4                          # large rows
+    kf[0, 1, 70:75] *= 1.0e-6                         # tiny rows
+    kf[0, 1, 200] = kf[0, 1, 50] * 2.0                # exact direction duplicate at another scale
+    qf = rng.standard_normal((1, 8, 8, 128)).astype(np.float32)
+    vf = rng.standard_normal((1, 2, 260, 128)).astype(np.float32)
+    w, q, k, v = _custom(kf, qf, vf, budget=180, pool_w=4, beta=1, sim_threshold=0.5, lam=0.1)
+    run_fused(w, q, k, v, [(0, 0), (0, 1)], "zeros", check_parts=True)
+
+
+def test_empty_batch_is_a_no_op():
+    shp = rkv.Shape(num_problems=0, kv_heads=8, q_heads=32, n_tokens=1152, budget=1024)
+    k = torch.empty((0, 8, 1152, 128), dtype=torch.bfloat16, device="cuda")
+    q = torch.empty((0, 32, 8, 128), dtype=torch.bfloat16, device="cuda")
+    say("empty batch")
+    st, ko, vo, idx, _ = rkv.rkv_compress(shp, q, k, k)
+    torch.cuda.synchronize()
+    assert st == rkv.RKV_OK and ko.shape == (0, 8, 1024, 128) and idx.shape == (0, 8, 1024)
