@@ -62,8 +62,11 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t l
                : "memory");
 }
 
-template <int NW, int RT, int TC>
-__global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
+template <int NW, int RT, int TC, int WPS>
+__global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
+  // WPS = waves per SIMD the register budget is cut for: 2 keeps two sets of key fragments and r_j
+  // (prefetch one subtile ahead), 3 keeps one set and relies on the other waves to hide LDS latency.
+  constexpr int KB = (WPS >= 3) ? 1 : 2;
   constexpr int NT = NW * 64;
   constexpr int BM = NW * RT * 32;
   constexpr int NS = TC / 32;                       // 32-key subtiles per tile
@@ -96,6 +99,7 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
   const float* rn = a.rnorm + (int64_t)head * a.n_pad;
   const int n = a.n;
   const int i0 = rb * BM + wave * (RT * 32);
+  const bool active = i0 < n;                        // wave-uniform: does this wave own any candidate row?
   const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)gram_lds);   // LDS byte address of the dynamic segment
   const uint32_t row_bytes = (uint32_t)a.kst * 2u;
 
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
     return acc;
   };
   // K_i . u = sum of the three pseudo-key columns (accumulator elements 0..2 of lanes with half == 0)
-  {
+  if (active) {
     bf16x8 pf[8];
     read_k(pf, gram_lds, 0);
 #pragma unroll
@@ -286,22 +290,30 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
     const unsigned char* tile = gram_lds + OFF_TILE + buf * TILE_SPAN;
     const float* rjs = reinterpret_cast<const float*>(gram_lds + OFF_RJ + buf * TC * 4);
 
-    bf16x8 kf[2][8];
-    float rj[2][16];
+    if (active) {
+    bf16x8 kf[KB][8];
+    float rj[KB][16];
     f32x16 acc[2];
-    read_k(kf[(NS - 1) & 1], tile, NS - 1);
-    read_rj(rj[(NS - 1) & 1], rjs, NS - 1);
+    read_k(kf[(NS - 1) % KB], tile, NS - 1);
+    read_rj(rj[(NS - 1) % KB], rjs, NS - 1);
     // software pipeline over the NS * RT tiles of this iteration: chain(q) with test(q - 1)
 #pragma unroll
     for (int q2 = 0; q2 <= NS * RT; ++q2) {
       if (q2 > 0) __builtin_amdgcn_sched_barrier(0);
       if (q2 < NS * RT) {
         const int s = NS - 1 - q2 / RT, rt = q2 % RT;
-        // prefetch the next subtile: its key fragments replace those of subtile s + 1 (all chains on
-        // them are issued); its r_j replace those of s + 1 one step later, after that subtile's last test
-        if (rt == 0 && s > 0) read_k(kf[(s - 1) & 1], tile, s - 1);
-        if (rt == 1 && s > 0) read_rj(rj[(s - 1) & 1], rjs, s - 1);
-        acc[q2 & 1] = chain(kf[s & 1], res[rt]);
+        if constexpr (KB == 2) {
+          // prefetch the next subtile: its key fragments replace those of subtile s + 1 (all chains on
+          // them are issued); its r_j replace those of s + 1 one step later, after that subtile's last test
+          if (rt == 0 && s > 0) read_k(kf[(s - 1) & 1], tile, s - 1);
+          if (rt == 1 && s > 0) read_rj(rj[(s - 1) & 1], rjs, s - 1);
+        } else {
+          // single set: fetch this subtile's fragments now (the previous subtile's chains are issued)
+          // and its r_j one step later (the previous subtile's last test ran in the step before)
+          if (rt == 0 && s < NS - 1) read_k(kf[0], tile, s);
+          if (rt == 1 && s < NS - 1) read_rj(rj[0], rjs, s);
+        }
+        acc[q2 & 1] = chain(kf[s % KB], res[rt]);
         // the next tile's DMA copies are spread over the steps instead of stalling the wave up front
         constexpr int PER_STEP = (LOADS / NW + NS * RT - 1) / (NS * RT);
 #pragma unroll
@@ -311,10 +323,15 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
       if (q2 > 0) {
         const int qp = q2 - 1;
         const int sp = NS - 1 - qp / RT, rtp = qp % RT;
-        const float m = tile_max(acc[qp & 1], rj[sp & 1]);
+        const float m = tile_max(acc[qp & 1], rj[sp % KB]);
         if (q2 < NS * RT) interleave();
-        if (__any(m > thr[rtp])) tile_hits(acc[qp & 1], rj[sp & 1], rtp, ct * TC + sp * 32);
+        if (__any(m > thr[rtp])) tile_hits(acc[qp & 1], rj[sp % KB], rtp, ct * TC + sp * 32);
       }
+    }
+    } else if (more) {
+      // a wave whose rows all lie past n only helps to copy the next tile
+#pragma unroll
+      for (int jj = 0; jj < LOADS / NW; ++jj) issue_rows(ct - 1, buf ^ 1, jj, std::false_type{});
     }
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -336,13 +353,13 @@ __global__ __launch_bounds__(NW * 64, 2) void gram_kernel(GramArgs a) {
   }
 }
 
-template <int NW, int RT, int TC>
+template <int NW, int RT, int TC, int WPS>
 hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   constexpr int BM = NW * RT * 32;
   constexpr size_t lds = kPseudoBytes + 2 * (size_t)TC * kRowBytes + 2 * (size_t)TC * 4;
   static bool configured = false;
   if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
@@ -350,7 +367,7 @@ hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   a.row_blocks = (pl.n + BM - 1) / BM;
   const int head_groups = (pl.heads + 7) / 8;
   const dim3 grid((unsigned)((int64_t)head_groups * a.row_blocks * 8));
-  hipLaunchKernelGGL((gram_kernel<NW, RT, TC>), grid, dim3(NW * 64), lds, stream, a);
+  hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS>), grid, dim3(NW * 64), lds, stream, a);
   return hipGetLastError();
 }
 
@@ -366,7 +383,11 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   a.T = pl.T; a.eps = pl.eps;
   a.row_blocks = 0;
-  return launch_shape<4, 2, 128>(a, pl, stream);
+#ifdef EXP_SHAPE
+  return launch_shape<EXP_SHAPE>(a, pl, stream);
+#else
+  return launch_shape<4, 2, 128, 2>(a, pl, stream);
+#endif
 }
 
 }  // namespace rkv
