@@ -71,6 +71,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sim-threshold", type=float, default=None)
     ap.add_argument("--beta", type=int, default=None)
+    ap.add_argument("--skip-saturated", action="store_true",
+                    help="set RKV_FLAG_SKIP_SATURATED (exact, data-dependent shortcut of the similarity pass); "
+                         "the roofline entry is then not meaningful and is omitted")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -99,7 +102,8 @@ def main() -> int:
     qd, kd, vd = dev(q), dev(k), dev(v)
     shp = rkv.Shape(num_problems=w.num_problems, kv_heads=w.kv_heads, q_heads=w.q_heads, n_tokens=w.n_tokens,
                     budget=w.budget, alpha=w.alpha, pool_w=w.pool_w, beta=w.beta,
-                    sim_threshold=w.sim_threshold, lam=w.lam, eps=w.eps)
+                    sim_threshold=w.sim_threshold, lam=w.lam, eps=w.eps,
+                    flags=rkv.RKV_FLAG_SKIP_SATURATED if args.skip_saturated else 0)
     ws = rkv.make_workspace(shp)
     oshape = (w.num_problems, w.kv_heads, w.budget, w.head_dim)
     ko = torch.empty(oshape, dtype=torch.bfloat16, device="cuda")
@@ -193,6 +197,10 @@ def main() -> int:
         "stages": {s: {kk: float(vv) for kk, vv in st.items()} for s, st in stages.items()},
         "roofline": roofline,
     }
+    if args.skip_saturated:
+        out["config"]["flags"] = "RKV_FLAG_SKIP_SATURATED"
+        out["roofline"] = None          # executed matrix work is data dependent in this mode
+        out["stages"]["gram"].pop("TFLOP/s"), out["stages"]["gram"].pop("frac_mfma")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, q, k, v, args.cpu_seconds)
     print(json.dumps(out))

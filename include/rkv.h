@@ -47,6 +47,14 @@ typedef enum {
   RKV_ERR_HIP = -6           /* a kernel launch failed (hipGetLastError) */
 } rkv_status;
 
+/*
+ * rkv_params.flags.  RKV_FLAG_SKIP_SATURATED: exact shortcut of the redundancy pass.  A token whose
+ * `beta` most recent similar tokens have been found cannot change any more (Sec. 3.3 zeroes only those
+ * beta entries), so a wave whose rows are all in that state stops forming similarity tiles.  Results
+ * are bit-identical to flags = 0; only the amount of matrix work differs (data dependent).
+ */
+#define RKV_FLAG_SKIP_SATURATED 1u
+
 typedef struct {
   int32_t num_problems;      /* P >= 0; an empty batch is valid and enqueues nothing */
   int32_t kv_heads;          /* H */
@@ -60,7 +68,7 @@ typedef struct {
   float   sim_threshold;     /* T, strict '>' (Sec. 3.3) */
   float   lambda;            /* trade-off of Eq. 7 (paper: 0.1) */
   float   eps;               /* added to the key norm (Eq. 5, paper: 1e-8) */
-  uint32_t flags;            /* must be 0 */
+  uint32_t flags;            /* 0 or RKV_FLAG_* bits */
   int64_t k_stride_problem, k_stride_head, k_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
   int64_t v_stride_problem, v_stride_head, v_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
 } rkv_params;

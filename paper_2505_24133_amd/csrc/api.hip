@@ -15,7 +15,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
     return RKV_ERR_SHAPE;
   if (q.q_heads % q.kv_heads != 0) return RKV_ERR_SHAPE;
   if (q.n_tokens <= q.alpha || q.budget <= q.alpha) return RKV_ERR_SHAPE;
-  if (q.head_dim != kHeadDim || q.flags != 0) return RKV_ERR_UNSUPPORTED;
+  if (q.head_dim != kHeadDim || (q.flags & ~(uint32_t)RKV_FLAG_SKIP_SATURATED) != 0) return RKV_ERR_UNSUPPORTED;
   const int G = q.q_heads / q.kv_heads;
   if (q.alpha > kMaxQRows || (int64_t)G * q.alpha > kMaxQRows || q.n_tokens > 32768) return RKV_ERR_UNSUPPORTED;
   if ((int64_t)q.num_problems * q.kv_heads > (1 << 22)) return RKV_ERR_UNSUPPORTED;
@@ -27,6 +27,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->P = q.num_problems; pl->H = q.kv_heads; pl->G = G; pl->N = q.n_tokens; pl->alpha = q.alpha;
   pl->n = q.n_tokens - q.alpha; pl->budget = q.budget; pl->k_sel = q.budget - q.alpha;
   pl->W = q.pool_w; pl->beta = q.beta; pl->T = q.sim_threshold; pl->lambda = q.lambda; pl->eps = q.eps;
+  pl->skip_saturated = (q.flags & RKV_FLAG_SKIP_SATURATED) != 0;
   pl->heads = q.num_problems * q.kv_heads;
   pl->chunks = (pl->n + kChunk - 1) / kChunk;
   pl->n_pad = pl->chunks * kChunk;

@@ -33,7 +33,7 @@ struct GramArgs {
   const float* rnorm;
   const float* upart;
   float* sbar;
-  int H, heads, n, n_pad, chunks, beta, row_blocks;
+  int H, heads, n, n_pad, chunks, beta, row_blocks, skip_saturated;
   int64_t ksp, ksh, kst;
   float T, eps;
 };
@@ -290,7 +290,16 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     const unsigned char* tile = gram_lds + OFF_TILE + buf * TILE_SPAN;
     const float* rjs = reinterpret_cast<const float*>(gram_lds + OFF_RJ + buf * TC * 4);
 
-    if (active) {
+    // Optional exact shortcut: once every row of the wave has met beta hits nothing it could still
+    // find changes its result, so the matrix work is skipped (the wave keeps copying tiles).
+    bool live = active;
+    if (a.skip_saturated && live) {
+      bool open = false;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) open = open || (thr[rt] != INFINITY);
+      live = __any(open);
+    }
+    if (live) {
     bf16x8 kf[KB][8];
     float rj[KB][16];
     f32x16 acc[2];
@@ -335,7 +344,17 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     }
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    if (a.skip_saturated) {
+      // leave the loop as soon as no wave of the workgroup has an open row (all copies have landed)
+      bool open = false;
+      if (active) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) open = open || (thr[rt] != INFINITY);
+      }
+      if (__syncthreads_or(open ? 1 : 0) == 0) break;
+    } else {
+      __syncthreads();
+    }
   }
 
   // ---- closed-form row sums minus the forgiven similarities
@@ -383,6 +402,7 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   a.T = pl.T; a.eps = pl.eps;
   a.row_blocks = 0;
+  a.skip_saturated = pl.skip_saturated ? 1 : 0;
 #ifdef EXP_SHAPE
   return launch_shape<EXP_SHAPE>(a, pl, stream);
 #else

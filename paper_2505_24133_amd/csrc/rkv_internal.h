@@ -25,6 +25,7 @@ struct Plan {
   int chunks;         // ceil(n / kChunk)
   int n_pad;          // chunks * kChunk
   float T, lambda, eps;
+  bool skip_saturated;     // RKV_FLAG_SKIP_SATURATED
   int64_t ksp, ksh, kst;   // key strides (elements)
   int64_t vsp, vsh, vst;   // value strides (elements)
   size_t off_rnorm;   // float [heads][n_pad]           1 / (|K_i| + eps), 0 for i >= n

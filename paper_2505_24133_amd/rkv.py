@@ -24,6 +24,7 @@ RKV_ERR_UNSUPPORTED = -3
 RKV_ERR_WORKSPACE = -4
 RKV_ERR_PARAM = -5
 RKV_ERR_HIP = -6
+RKV_FLAG_SKIP_SATURATED = 1
 
 
 class RkvParams(ctypes.Structure):
@@ -91,10 +92,11 @@ class Shape:
     sim_threshold: float = 0.5
     lam: float = 0.1
     eps: float = 1e-8
+    flags: int = 0
 
     def params(self, k: Optional[torch.Tensor] = None, v: Optional[torch.Tensor] = None) -> RkvParams:
         p = RkvParams(self.num_problems, self.kv_heads, self.q_heads, self.n_tokens, self.head_dim, self.alpha,
-                      self.budget, self.pool_w, self.beta, self.sim_threshold, self.lam, self.eps, 0,
+                      self.budget, self.pool_w, self.beta, self.sim_threshold, self.lam, self.eps, self.flags,
                       0, 0, 0, 0, 0, 0)
         if k is not None:
             p.k_stride_problem, p.k_stride_head, p.k_stride_token = k.stride(0), k.stride(1), k.stride(2)

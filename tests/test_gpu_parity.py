@@ -370,3 +370,27 @@ def test_empty_batch_is_a_no_op():
     st, ko, vo, idx, _ = rkv.rkv_compress(shp, q, k, k)
     torch.cuda.synchronize()
     assert st == rkv.RKV_OK and ko.shape == (0, 8, 1024, 128) and idx.shape == (0, 8, 1024)
+
+
+def test_skip_saturated_flag_gives_bit_identical_results():
+    """RKV_FLAG_SKIP_SATURATED only skips similarity tiles that cannot change a result."""
+    cases = [synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=4),
+             synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=2, sim_threshold=0.95, beta=2),
+             synth.scaled(synth.CONFIGS["cfg5_llama8b_b8192_bs4"], num_problems=1),
+             synth.CONFIGS["cfg1_tiny"]]
+    for w in cases:
+        P = w.num_problems
+        q, k, v = synth.make_batch(w)
+        qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+        dense = shape_of(w, P)
+        skip = shape_of(w, P)
+        skip.flags = rkv.RKV_FLAG_SKIP_SATURATED
+        say(f"skip-saturated vs dense: {w.name} P={P} T={w.sim_threshold} beta={w.beta}")
+        a = rkv.rkv_compress(dense, qd, kd, vd, want_score=True)
+        b = rkv.rkv_compress(skip, qd, kd, vd, want_score=True)
+        ra, ma = rkv.rkv_score_redundancy(dense, kd, want_mean_sim=True)
+        rb, mb = rkv.rkv_score_redundancy(skip, kd, want_mean_sim=True)
+        torch.cuda.synchronize()
+        for x, y in zip(a[1:], b[1:]):
+            assert torch.equal(x, y)
+        assert torch.equal(ra, rb) and torch.equal(ma, mb)
