@@ -147,21 +147,39 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
       const int cols = min(block_cols, n - cb);
       const int width = cols + halo;
       const int first = cb - a.W;                              // column held at pool[j][0]
-      for (int j = 0; j < a.alpha; ++j) {
-        const float* row = lg + (int64_t)j * a.n_pad;
-        for (int c = t; c < width; c += kFinThreads) {
-          const int col = first + c;
-          pool[j * width + c] = (col >= 0 && col < n) ? row[col] : -INFINITY;
+      // eight independent loads per thread are in flight before the first LDS store
+      const int total = a.alpha * width;
+      for (int base = 0; base < total; base += 8 * kFinThreads) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int idx = base + u * kFinThreads + t;
+          const int j = idx / width;
+          const int col = first + (idx - j * width);
+          v[u] = (idx < total && col >= 0 && col < n) ? lg[(int64_t)j * a.n_pad + col] : -INFINITY;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int idx = base + u * kFinThreads + t;
+          if (idx < total) pool[idx] = v[u];
         }
       }
       __syncthreads();
       for (int li = t; li < cols; li += kFinThreads) {
         float imp = 0.f;
-        for (int j = 0; j < a.alpha; ++j) {
-          const float* wrow = pool + j * width + li;          // window [i - W, i + W - 1] starts here
-          float m = wrow[0];
-          for (int c = 1; c < win; ++c) m = fmaxf(m, wrow[c]);
-          imp += expf(m - gmax[j]) * ginv[j];
+        // eight query rows at a time: their window reads are independent LDS loads
+        for (int j0 = 0; j0 < a.alpha; j0 += 8) {
+          float m[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) m[u] = -INFINITY;
+          for (int c = 0; c < win; ++c) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+              if (j0 + u < a.alpha) m[u] = fmaxf(m[u], pool[(j0 + u) * width + li + c]);   // window [i - W, i + W - 1]
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (j0 + u < a.alpha) imp += __expf(m[u] - gmax[j0 + u]) * ginv[j0 + u];
         }
         imp_dst[cb + li] = imp;
       }
@@ -178,7 +196,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
     }
     if constexpr ((MODE & kModeRedundancy) != 0) {
       const float s = sb[i];
-      rd = expf(s - smax) * sinv;
+      rd = __expf(s - smax) * sinv;
       if (a.red_out) a.red_out[(int64_t)head * n + i] = rd;
       if (a.sbar_out) a.sbar_out[(int64_t)head * n + i] = s;
     } else if constexpr ((MODE & kModeSelect) != 0) {
