@@ -24,6 +24,7 @@
  *     the outputs are untouched (after RKV_ERR_HIP earlier stages of the call may have run).
  *   - Inputs holding NaN or Inf give unspecified scores (never out-of-bounds accesses).
  *   - Supported shapes: d == 128, 1 <= alpha <= 64, G * alpha <= 64, N <= 32768,
+ *     pool_w <= 1000 and alpha * 2 * pool_w <= 16384,
  *     token strides multiples of 8 elements (16-byte aligned rows).
  */
 #ifndef RKV_H

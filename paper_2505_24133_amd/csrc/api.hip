@@ -22,7 +22,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   if (!(q.lambda >= 0.f && q.lambda <= 1.f) || !(q.sim_threshold >= 0.f && q.sim_threshold <= 1.f) ||
       !(q.eps >= 0.f) || !isfinite(q.eps) || q.beta < 0 || q.pool_w < 0)
     return RKV_ERR_PARAM;
-  if ((int64_t)q.alpha * (q.pool_w > 0 ? 2 * (int64_t)q.pool_w : 1) > 16384) return RKV_ERR_UNSUPPORTED;
+  if ((int64_t)q.alpha * (q.pool_w > 0 ? 2 * (int64_t)q.pool_w : 1) > 16384 || q.pool_w > 1000) return RKV_ERR_UNSUPPORTED;
 
   pl->P = q.num_problems; pl->H = q.kv_heads; pl->G = G; pl->N = q.n_tokens; pl->alpha = q.alpha;
   pl->n = q.n_tokens - q.alpha; pl->budget = q.budget; pl->k_sel = q.budget - q.alpha;

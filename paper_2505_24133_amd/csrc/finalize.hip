@@ -142,27 +142,31 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
     float* pool = reinterpret_cast<float*>(keys);            // the key buffer is not in use yet
     const int win = (a.W > 0) ? 2 * a.W : 1;
     const int halo = win - 1;
-    const int block_cols = a.pool_floats / a.alpha - halo;    // >= 1 (checked on the host)
+    const int block_cols = min(a.pool_floats / a.alpha, 2 * kFinThreads) - halo;    // >= 1 (checked on the host)
     for (int cb = 0; cb < n; cb += block_cols) {
       const int cols = min(block_cols, n - cb);
       const int width = cols + halo;
       const int first = cb - a.W;                              // column held at pool[j][0]
-      // eight independent loads per thread are in flight before the first LDS store
-      const int total = a.alpha * width;
-      for (int base = 0; base < total; base += 8 * kFinThreads) {
-        float v[8];
+      // four query rows x two column slots: eight independent loads per thread are in flight
+      // before the first LDS store (width <= 2 * kFinThreads by the choice of block_cols)
+      for (int j0 = 0; j0 < a.alpha; j0 += 4) {
+        float v[4][2];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int idx = base + u * kFinThreads + t;
-          const int j = idx / width;
-          const int col = first + (idx - j * width);
-          v[u] = (idx < total && col >= 0 && col < n) ? lg[(int64_t)j * a.n_pad + col] : -INFINITY;
-        }
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int idx = base + u * kFinThreads + t;
-          if (idx < total) pool[idx] = v[u];
-        }
+          for (int sl = 0; sl < 2; ++sl) {
+            const int c = t + sl * kFinThreads;
+            const int col = first + c;
+            v[u][sl] = (j0 + u < a.alpha && c < width && col >= 0 && col < n)
+                           ? lg[(int64_t)(j0 + u) * a.n_pad + col] : -INFINITY;
+          }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int sl = 0; sl < 2; ++sl) {
+            const int c = t + sl * kFinThreads;
+            if (j0 + u < a.alpha && c < width) pool[(j0 + u) * width + c] = v[u][sl];
+          }
       }
       __syncthreads();
       for (int li = t; li < cols; li += kFinThreads) {
