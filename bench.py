@@ -24,6 +24,11 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK = 2.5e15      # MI355X dense bf16, flop/s
 HBM_PEAK = 8.0e12            # B/s
 
+# HBM bytes per launch of the similarity (Gram) kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this same command, scaled by a plain 256 MiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 KiB);
+# the runs are summarised in profiles/rkv_compress_cfg2_counters.md.
+GRAM_TRAFFIC_BYTES = {"cfg2_llama8b_b1024": int((4.298e4 * 2.0 + 1144) * 1024)}
+
 
 def hip_runtime(torch):
     """The HIP runtime already loaded by torch (used here only for event timing)."""
@@ -71,6 +76,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sim-threshold", type=float, default=None)
     ap.add_argument("--beta", type=int, default=None)
+    ap.add_argument("--lam", type=float, default=None, help="lambda of Eq. 7 (1.0 = attention-only eviction, similarity pass skipped)")
     ap.add_argument("--skip-saturated", action="store_true",
                     help="set RKV_FLAG_SKIP_SATURATED (exact, data-dependent shortcut of the similarity pass); "
                          "the roofline entry is then not meaningful and is omitted")
@@ -94,6 +100,8 @@ def main() -> int:
         w = synth.scaled(w, sim_threshold=args.sim_threshold)
     if args.beta is not None:
         w = synth.scaled(w, beta=args.beta)
+    if args.lam is not None:
+        w = synth.scaled(w, lam=args.lam)
     q, k, v = synth.make_batch(w)
 
     def dev(bits):
@@ -170,11 +178,14 @@ def main() -> int:
         "finalize_select": {"ms": avg[2], "GB/s": select_bytes / avg[2] / 1e6, "frac_hbm": select_bytes / (avg[2] * 1e-3) / HBM_PEAK},
         "gather": {"ms": avg[3], "GB/s": gather_bytes / avg[3] / 1e6, "frac_hbm": gather_bytes / (avg[3] * 1e-3) / HBM_PEAK},
     }
+    if w.lam == 1.0:                     # attention-only: the similarity pass is not run
+        stages["gram"] = {"ms": avg[1]}
     dominant = max(stages, key=lambda s: stages[s]["ms"])
     if dominant == "gram":
         roofline = {"kernel": "gram_kernel", "bound": "mfma", "achieved": gram_flops / (avg[1] * 1e-3) / 1e12,
                     "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
-                    "frac": gram_flops / (avg[1] * 1e-3) / MFMA_BF16_PEAK, "traffic": None}
+                    "frac": gram_flops / (avg[1] * 1e-3) / MFMA_BF16_PEAK,
+                    "traffic": GRAM_TRAFFIC_BYTES.get(w.name) if args.sim_threshold is None and args.beta is None else None}
     else:
         b = {"prepass": prepass_bytes, "finalize_select": select_bytes, "gather": gather_bytes}[dominant]
         i = ["prepass", "gram", "finalize_select", "gather"].index(dominant)

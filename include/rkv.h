@@ -117,7 +117,8 @@ rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, cons
  * The whole step (Sec. 3.1-3.4, Alg. 1): the four calls above back to back on `stream`
  * without host synchronisation.  kept_idx [P, H, budget] and score [P, H, n] are optional
  * outputs (NULL to skip).  Returns RKV_NOT_TRIGGERED without enqueuing anything when
- * N <= budget.
+ * N <= budget.  With lambda == 1 the score of Eq. 7 is the importance alone (attention-only
+ * eviction, the baseline of Sec. 4) and the similarity pass is skipped.
  */
 rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
                         void* k_out, void* v_out, int32_t* kept_idx, float* score,

@@ -126,6 +126,23 @@ def mean_similarity(k_cand: np.ndarray, T: float, beta: int, eps: float) -> np.n
     return S.sum(axis=1) / S.shape[0]
 
 
+def mean_similarity_rows(k_cand: np.ndarray, rows, T: float, beta: int, eps: float) -> np.ndarray:
+    """Eq. 5-6 for a few tokens only (sizes where the full n x n matrix is too large to hold):
+    the same definition as ``mean_similarity``, one row of S at a time."""
+    n = k_cand.shape[0]
+    norm = np.sqrt((k_cand * k_cand).sum(axis=1, keepdims=True))
+    kbar = k_cand / (norm + eps)
+    out = []
+    for i in rows:
+        s = kbar @ kbar[i]                       # S[i, :]
+        s[i] = 0.0
+        similar = np.nonzero(s > T)[0]           # ascending, so the most recent are at the end
+        if beta > 0:
+            s[similar[-beta:]] = 0.0
+        out.append(s.sum() / n)
+    return np.array(out)
+
+
 def redundancy(k_cand: np.ndarray, T: float, beta: int, eps: float) -> np.ndarray:
     """Eq. 6: R = softmax over the n candidates of S-bar."""
     return softmax_rows(mean_similarity(k_cand, T, beta, eps)[None, :])[0]

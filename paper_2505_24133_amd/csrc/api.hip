@@ -162,10 +162,13 @@ static rkv_status compress_impl(const rkv_params* prm, const void* q_obs, const 
   if ((s = mark(0)) != RKV_OK) return s;
   if ((s = hip_status(launch_prepass(pl, q_obs, k, w, st))) != RKV_OK) return s;
   if ((s = mark(1)) != RKV_OK) return s;
-  if ((s = hip_status(launch_gram(pl, k, w, st))) != RKV_OK) return s;
+  // lambda == 1 makes Eq. 7 the importance score alone (attention-only eviction): the similarity
+  // pass cannot influence the result and is not run.
+  const bool attention_only = (pl.lambda == 1.0f);
+  if (!attention_only && (s = hip_status(launch_gram(pl, k, w, st))) != RKV_OK) return s;
   if ((s = mark(2)) != RKV_OK) return s;
-  if ((s = hip_status(launch_finalize(pl, kModeImportance | kModeRedundancy | kModeSelect, w, nullptr, nullptr,
-                                      nullptr, nullptr, nullptr, score, idx, st))) != RKV_OK)
+  const int mode = attention_only ? (kModeImportance | kModeSelect) : (kModeImportance | kModeRedundancy | kModeSelect);
+  if ((s = hip_status(launch_finalize(pl, mode, w, nullptr, nullptr, nullptr, nullptr, nullptr, score, idx, st))) != RKV_OK)
     return s;
   if ((s = mark(3)) != RKV_OK) return s;
   if ((s = hip_status(launch_gather(pl, k, v, idx, k_out, v_out, st))) != RKV_OK) return s;

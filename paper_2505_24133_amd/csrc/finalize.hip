@@ -204,7 +204,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
       if (a.red_out) a.red_out[(int64_t)head * n + i] = rd;
       if (a.sbar_out) a.sbar_out[(int64_t)head * n + i] = s;
     } else if constexpr ((MODE & kModeSelect) != 0) {
-      rd = a.red_in[(int64_t)head * n + i];
+      rd = a.red_in ? a.red_in[(int64_t)head * n + i] : 0.f;      // no redundancy input: attention-only score
     }
     if constexpr ((MODE & kModeSelect) != 0) {
       const float z = a.lambda * imp - (1.0f - a.lambda) * rd;
@@ -325,6 +325,8 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
     case kModeImportance: return launch_mode<kModeImportance>(a, pl.heads, lds, stream);
     case kModeRedundancy: return launch_mode<kModeRedundancy>(a, pl.heads, lds, stream);
     case kModeSelect: return launch_mode<kModeSelect>(a, pl.heads, lds, stream);
+    case kModeImportance | kModeSelect:
+      return launch_mode<kModeImportance | kModeSelect>(a, pl.heads, lds, stream);
     case kModeImportance | kModeRedundancy | kModeSelect:
       return launch_mode<kModeImportance | kModeRedundancy | kModeSelect>(a, pl.heads, lds, stream);
     default: return hipErrorInvalidValue;

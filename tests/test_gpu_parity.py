@@ -394,3 +394,40 @@ def test_skip_saturated_flag_gives_bit_identical_results():
         for x, y in zip(a[1:], b[1:]):
             assert torch.equal(x, y)
         assert torch.equal(ra, rb) and torch.equal(ma, mb)
+
+
+def test_largest_supported_cache_sampled_rows():
+    """N = 32768 (the largest supported): 256 column tiles, 128 row blocks.  The oracle checks sampled
+    tokens one by one (mean similarity from single rows of S) and every structural property of the
+    output; the selection is checked against the GPU's own scores."""
+    N, budget, alpha = 32768, 32640, 8
+    w = synth.Workload("max", 1, 1, 4, N, budget, alpha=alpha, seed=91, recipe="clusters", n_clusters=4096,
+                       cluster_sigma=0.25, pool_w=4, beta=1, sim_threshold=0.8, lam=0.1)
+    q, k, v = synth.make_batch(w)
+    shp = shape_of(w, 1)
+    qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    say("max size: rkv_score_redundancy + rkv_compress N=32768")
+    red, msim = rkv.rkv_score_redundancy(shp, kd, want_mean_sim=True)
+    st, ko, vo, idx, score = rkv.rkv_compress(shp, qd, kd, vd, want_score=True)
+    torch.cuda.synchronize()
+    n = w.n_cand
+    kc = O.decode_bf16(k[0, 0][:n])
+    rows = [0, 1, 127, 128, 4095, 9999, 16384, 20000, 32000, n - 129, n - 2, n - 1]
+    ref = O.mean_similarity_rows(kc, rows, float(np.float32(w.sim_threshold)), w.beta, w.eps)
+    got = msim[0, 0].cpu().numpy()[rows]
+    # a sampled row is exempt only if one of its similarities sits within the fp32 band around T
+    norm = np.sqrt((kc * kc).sum(1, keepdims=True)); kbar = kc / (norm + w.eps)
+    for r_i, (i, g, e) in enumerate(zip(rows, got, ref)):
+        srow = kbar @ kbar[i]; srow[i] = 0.0
+        if np.any(np.abs(srow - w.sim_threshold) <= Hp.SIM_BAND):
+            continue
+        assert abs(g - e) <= 2e-6 + 1e-3 * abs(e), f"row {i}: gpu {g} oracle {e}"
+    z = score[0, 0].cpu().numpy()
+    kept = idx[0, 0].cpu().numpy()
+    np.testing.assert_array_equal(kept[:w.k_sel], Hp.exact_topk(z, w.k_sel))
+    np.testing.assert_array_equal(kept[w.k_sel:], np.arange(n, N))
+    np.testing.assert_array_equal(host_bits(ko)[0, 0], k[0, 0][kept])
+    np.testing.assert_array_equal(host_bits(vo)[0, 0], v[0, 0][kept])
+    r = red[0, 0].cpu().numpy().astype(np.float64)
+    assert abs(r.sum() - 1.0) < 1e-4                      # softmax over the candidates (Eq. 6)
+    np.testing.assert_allclose(r, np.exp(msim[0, 0].cpu().numpy().astype(np.float64) - np.log(np.exp(msim[0, 0].cpu().numpy().astype(np.float64)).sum())), rtol=1e-4)

@@ -224,6 +224,22 @@ def test_recency_rule_brute_force(seed):
                                brute_mean_similarity(k, T, beta, 1e-8), rtol=1e-11, atol=1e-14)
 
 
+def test_row_wise_mean_similarity_matches_full_and_brute_force():
+    rng = np.random.default_rng(31)
+    n, d = 40, 8
+    k = rng.standard_normal((n, d))
+    for i in (3, 9, 21):
+        k[i + 10] = k[i] + 0.02 * rng.standard_normal(d)
+    rows = [0, 3, 13, 19, 31, 39]
+    for T, beta in [(0.5, 1), (0.3, 3), (0.9, 0), (0.0, 2)]:
+        got = O.mean_similarity_rows(k, rows, T, beta, 1e-8)
+        np.testing.assert_allclose(got, O.mean_similarity(k, T, beta, 1e-8)[rows], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(got, brute_mean_similarity(k, T, beta, 1e-8)[rows], rtol=1e-11, atol=1e-14)
+    g = read_golden("recency_rule_three_keys.txt")
+    k3 = g["keys"].reshape(3, 2)
+    np.testing.assert_allclose(O.mean_similarity_rows(k3, [0, 1, 2], 0.5, 1, 0.0), g["mean_sim"], rtol=1e-12)
+
+
 @pytest.mark.parametrize("T,beta", [(0.5, 0), (1.0, 3), (1.5, 1)])
 def test_closed_form_when_nothing_is_forgiven(T, beta):
     """beta = 0 or T >= 1: n * mean_sim_i = r_i K_i . u - (r_i |K_i|)^2 with u = sum_j r_j K_j."""
