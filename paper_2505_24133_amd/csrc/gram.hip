@@ -285,8 +285,10 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   for (int it = 0; it < nct; ++it) {
     const int ct = nct - 1 - it;
     const int buf = it & 1;
-    const bool more = it + 1 < nct;
-    if (more) issue_rj(ct - 1, buf ^ 1);
+    // The next tile is copied while this one is used.  The last iteration copies tile 0 once more
+    // (harmless, never read) so that the copy needs no branch inside the MFMA/VALU pipeline below.
+    const int ctn = max(ct - 1, 0);
+    issue_rj(ctn, buf ^ 1);
     const unsigned char* tile = gram_lds + OFF_TILE + buf * TILE_SPAN;
     const float* rjs = reinterpret_cast<const float*>(gram_lds + OFF_RJ + buf * TC * 4);
 
@@ -327,7 +329,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
         constexpr int PER_STEP = (LOADS / NW + NS * RT - 1) / (NS * RT);
 #pragma unroll
         for (int d = 0; d < PER_STEP; ++d)
-          if (more && q2 * PER_STEP + d < LOADS / NW) issue_rows(ct - 1, buf ^ 1, q2 * PER_STEP + d, std::false_type{});
+          if (q2 * PER_STEP + d < LOADS / NW) issue_rows(ctn, buf ^ 1, q2 * PER_STEP + d, std::false_type{});
       }
       if (q2 > 0) {
         const int qp = q2 - 1;
@@ -337,10 +339,10 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
         if (__any(m > thr[rtp])) tile_hits(acc[qp & 1], rj[sp % KB], rtp, ct * TC + sp * 32);
       }
     }
-    } else if (more) {
-      // a wave whose rows all lie past n only helps to copy the next tile
+    } else {
+      // a wave without open rows only helps to copy the next tile
 #pragma unroll
-      for (int jj = 0; jj < LOADS / NW; ++jj) issue_rows(ct - 1, buf ^ 1, jj, std::false_type{});
+      for (int jj = 0; jj < LOADS / NW; ++jj) issue_rows(ctn, buf ^ 1, jj, std::false_type{});
     }
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
