@@ -72,6 +72,7 @@ typedef struct {
   uint32_t flags;            /* 0 or RKV_FLAG_* bits */
   int64_t k_stride_problem, k_stride_head, k_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
   int64_t v_stride_problem, v_stride_head, v_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
+  int64_t o_stride_problem, o_stride_head, o_stride_token;   /* of k_out and v_out; 0,0,0 = dense [P,H,budget,d] */
 } rkv_params;
 
 /* Bytes of device scratch any entry point below needs for these params. */
@@ -107,7 +108,8 @@ rkv_status rkv_select_topk(const rkv_params* prm, const float* importance, const
 
 /*
  * Compaction (Alg. 1, gather + concatenate): k_out[p, h, r, :] = k[p, h, kept_idx[p, h, r], :],
- * likewise v.  k_out, v_out are dense [P, H, budget, d] bf16 and must not overlap k, v.
+ * likewise v.  k_out, v_out are [P, H, budget, d] bf16 (dense unless o_stride_* are set, e.g. to write
+ * into the first `budget` rows of a second cache allocation) and must not overlap k, v.
  * Every index must lie in [0, N); indices outside are clamped into that range.
  */
 rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, const int32_t* kept_idx,
@@ -133,6 +135,24 @@ rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k,
 rkv_status rkv_compress_events(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
                                void* k_out, void* v_out, int32_t* kept_idx, float* score,
                                void* ws, size_t ws_bytes, void* stream, void* const* events);
+
+/*
+ * Decode-loop bookkeeping (Sec. 3.1; query cache of App. C.1).  The cache holds up to
+ * N = n_tokens = B_budget + B_buffer rows per head; a decode step appends one row.
+ *
+ * rkv_should_compress: host-only trigger test of Alg. 1.  Returns RKV_OK when `cached_tokens` rows
+ * are held and the buffer is full (cached_tokens >= N > budget), RKV_NOT_TRIGGERED otherwise.
+ *
+ * rkv_cache_append: writes the new token's key/value rows k_new, v_new [P, kv_heads, d] at row
+ * `position` (0 <= position < N) of k_cache, v_cache [P, kv_heads, N, d] (strides from rkv_params)
+ * and its query state q_new [P, q_heads, d] into slot `q_slot` (0 <= q_slot < alpha) of the query
+ * cache q_cache [P, q_heads, alpha, d], which is what rkv_compress takes as q_obs (the importance
+ * score does not depend on the order of the alpha slots).  All bf16, device pointers.
+ */
+rkv_status rkv_should_compress(const rkv_params* prm, int32_t cached_tokens);
+rkv_status rkv_cache_append(const rkv_params* prm, void* k_cache, void* v_cache, void* q_cache,
+                            const void* k_new, const void* v_new, const void* q_new,
+                            int32_t position, int32_t q_slot, void* stream);
 
 /* Static, NUL-terminated description of a status value. */
 const char* rkv_status_string(rkv_status s);

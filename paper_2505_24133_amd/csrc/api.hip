@@ -45,6 +45,11 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   };
   if (!strides(q.k_stride_problem, q.k_stride_head, q.k_stride_token, &pl->ksp, &pl->ksh, &pl->kst)) return RKV_ERR_SHAPE;
   if (!strides(q.v_stride_problem, q.v_stride_head, q.v_stride_token, &pl->vsp, &pl->vsh, &pl->vst)) return RKV_ERR_SHAPE;
+  if (q.o_stride_problem == 0 && q.o_stride_head == 0 && q.o_stride_token == 0) {
+    pl->ost = kHeadDim; pl->osh = (int64_t)q.budget * kHeadDim; pl->osp = pl->osh * q.kv_heads;
+  } else {
+    if (!strides(q.o_stride_problem, q.o_stride_head, q.o_stride_token, &pl->osp, &pl->osh, &pl->ost)) return RKV_ERR_SHAPE;
+  }
 
   size_t off = 0;
   const size_t heads = (size_t)pl->heads, np = (size_t)pl->n_pad;
@@ -188,6 +193,29 @@ rkv_status rkv_compress_events(const rkv_params* prm, const void* q_obs, const v
   for (int i = 0; i < 5; ++i)
     if (events[i] == nullptr) return RKV_ERR_NULL;
   return compress_impl(prm, q_obs, k, v, k_out, v_out, kept_idx, score, ws, ws_bytes, stream, events);
+}
+
+rkv_status rkv_should_compress(const rkv_params* prm, int32_t cached_tokens) {
+  Plan pl;
+  const rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  // Alg. 1: compress once the rows held beyond the budget fill the buffer (here N = budget + buffer)
+  return (cached_tokens >= pl.N && pl.N > pl.budget) ? RKV_OK : RKV_NOT_TRIGGERED;
+}
+
+rkv_status rkv_cache_append(const rkv_params* prm, void* k_cache, void* v_cache, void* q_cache,
+                            const void* k_new, const void* v_new, const void* q_new,
+                            int32_t position, int32_t q_slot, void* stream) {
+  Plan pl;
+  const rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  if (empty(pl)) return RKV_OK;
+  if (k_cache == nullptr || v_cache == nullptr || q_cache == nullptr || k_new == nullptr || v_new == nullptr ||
+      q_new == nullptr)
+    return RKV_ERR_NULL;
+  if (position < 0 || position >= pl.N || q_slot < 0 || q_slot >= pl.alpha) return RKV_ERR_SHAPE;
+  return hip_status(launch_append(pl, k_cache, v_cache, q_cache, k_new, v_new, q_new, position, q_slot,
+                                  static_cast<hipStream_t>(stream)));
 }
 
 const char* rkv_status_string(rkv_status s) {

@@ -18,7 +18,7 @@ struct GatherArgs {
   uint16_t* k_out;
   uint16_t* v_out;
   int H, N, budget, blocks_per_head;
-  int64_t ksp, ksh, kst, vsp, vsh, vst;
+  int64_t ksp, ksh, kst, vsp, vsh, vst, osp, osh, ost;
 };
 
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
 #pragma unroll
   for (int m = 0; m < kRowsPerThread; ++m) {
     if (rows[m] < a.budget) {
-      const int64_t o = ((int64_t)head * a.budget + rows[m]) * kHeadDim + c16 * 8;
+      const int64_t o = p * a.osp + h * a.osh + (int64_t)rows[m] * a.ost + c16 * 8;
       *reinterpret_cast<uint4*>(a.k_out + o) = kr[m];
       *reinterpret_cast<uint4*>(a.v_out + o) = vr[m];
     }
@@ -69,6 +69,7 @@ hipError_t launch_gather(const Plan& pl, const void* k, const void* v, const int
   a.blocks_per_head = (pl.budget + kRowsPerBlock - 1) / kRowsPerBlock;
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   a.vsp = pl.vsp; a.vsh = pl.vsh; a.vst = pl.vst;
+  a.osp = pl.osp; a.osh = pl.osh; a.ost = pl.ost;
   const dim3 grid((unsigned)((int64_t)pl.heads * a.blocks_per_head));
   hipLaunchKernelGGL(gather_kernel, grid, dim3(kGatherThreads), 0, stream, a);
   return hipGetLastError();

@@ -28,6 +28,7 @@ struct Plan {
   bool skip_saturated;     // RKV_FLAG_SKIP_SATURATED
   int64_t ksp, ksh, kst;   // key strides (elements)
   int64_t vsp, vsh, vst;   // value strides (elements)
+  int64_t osp, osh, ost;   // strides of the compacted outputs (elements)
   size_t off_rnorm;   // float [heads][n_pad]           1 / (|K_i| + eps), 0 for i >= n
   size_t off_upart;   // float [heads][chunks][128]     per-chunk sums of r_i K_i
   size_t off_logit;   // float [heads][alpha][n_pad]    group-max scaled logits
@@ -57,6 +58,9 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
                            float* score_out, int32_t* kept_idx, hipStream_t stream);
 hipError_t launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* kept_idx,
                          void* k_out, void* v_out, hipStream_t stream);
+
+hipError_t launch_append(const Plan& pl, void* k_cache, void* v_cache, void* q_ring, const void* k_new,
+                         const void* v_new, const void* q_new, int pos, int slot, hipStream_t stream);
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 

@@ -37,6 +37,7 @@ class RkvParams(ctypes.Structure):
         ("flags", ctypes.c_uint32),
         ("k_stride_problem", ctypes.c_int64), ("k_stride_head", ctypes.c_int64), ("k_stride_token", ctypes.c_int64),
         ("v_stride_problem", ctypes.c_int64), ("v_stride_head", ctypes.c_int64), ("v_stride_token", ctypes.c_int64),
+        ("o_stride_problem", ctypes.c_int64), ("o_stride_head", ctypes.c_int64), ("o_stride_token", ctypes.c_int64),
     ]
 
 
@@ -65,8 +66,10 @@ def load_library() -> ctypes.CDLL:
     lib.rkv_compact.argtypes = [P, V, V, V, V, V, V]
     lib.rkv_compress.argtypes = [P, V, V, V, V, V, V, V, V, S, V]
     lib.rkv_compress_events.argtypes = [P, V, V, V, V, V, V, V, V, S, V, ctypes.POINTER(ctypes.c_void_p)]
+    lib.rkv_should_compress.argtypes = [P, ctypes.c_int32]
+    lib.rkv_cache_append.argtypes = [P, V, V, V, V, V, V, ctypes.c_int32, ctypes.c_int32, V]
     for name in ("rkv_workspace_size", "rkv_score_importance", "rkv_score_redundancy", "rkv_select_topk",
-                 "rkv_compact", "rkv_compress", "rkv_compress_events"):
+                 "rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_should_compress", "rkv_cache_append"):
         getattr(lib, name).restype = ctypes.c_int
     lib.rkv_status_string.argtypes = [ctypes.c_int]
     lib.rkv_status_string.restype = ctypes.c_char_p
@@ -94,14 +97,17 @@ class Shape:
     eps: float = 1e-8
     flags: int = 0
 
-    def params(self, k: Optional[torch.Tensor] = None, v: Optional[torch.Tensor] = None) -> RkvParams:
+    def params(self, k: Optional[torch.Tensor] = None, v: Optional[torch.Tensor] = None,
+               out: Optional[torch.Tensor] = None) -> RkvParams:
         p = RkvParams(self.num_problems, self.kv_heads, self.q_heads, self.n_tokens, self.head_dim, self.alpha,
                       self.budget, self.pool_w, self.beta, self.sim_threshold, self.lam, self.eps, self.flags,
-                      0, 0, 0, 0, 0, 0)
+                      0, 0, 0, 0, 0, 0, 0, 0, 0)
         if k is not None:
             p.k_stride_problem, p.k_stride_head, p.k_stride_token = k.stride(0), k.stride(1), k.stride(2)
         if v is not None:
             p.v_stride_problem, p.v_stride_head, p.v_stride_token = v.stride(0), v.stride(1), v.stride(2)
+        if out is not None and not out.is_contiguous():
+            p.o_stride_problem, p.o_stride_head, p.o_stride_token = out.stride(0), out.stride(1), out.stride(2)
         return p
 
     @property
@@ -133,6 +139,43 @@ def _check_q(shape: Shape, q: torch.Tensor) -> None:
     want = (shape.num_problems, shape.q_heads, shape.alpha, shape.head_dim)
     if tuple(q.shape) != want or q.dtype != torch.bfloat16 or not q.is_contiguous():
         raise ValueError(f"q_obs must be contiguous bf16 {want}")
+
+
+def _check_out(shape: Shape, k_out: torch.Tensor, v_out: torch.Tensor) -> None:
+    want = (shape.num_problems, shape.kv_heads, shape.budget, shape.head_dim)
+    for t in (k_out, v_out):
+        if tuple(t.shape) != want or t.dtype != torch.bfloat16 or t.stride(3) != 1:
+            raise ValueError(f"k_out / v_out must be bf16 {want} with a contiguous last dimension")
+    if k_out.stride() != v_out.stride():
+        raise ValueError("k_out and v_out must share their strides")
+
+
+def rkv_should_compress(shape: Shape, cached_tokens: int) -> bool:
+    """Trigger test of the decode loop: True once the buffer behind the budget is full."""
+    prm = shape.params()
+    s = load_library().rkv_should_compress(ctypes.byref(prm), int(cached_tokens))
+    if s < 0:
+        raise RkvError(s, "rkv_should_compress")
+    return s == RKV_OK
+
+
+def rkv_cache_append(shape: Shape, k_cache: torch.Tensor, v_cache: torch.Tensor, q_cache: torch.Tensor,
+                     k_new: torch.Tensor, v_new: torch.Tensor, q_new: torch.Tensor, position: int, q_slot: int) -> None:
+    """Write one decoded token's key/value rows at `position` and its query state into slot `q_slot`."""
+    _need_gpu(k_cache, v_cache, q_cache, k_new, v_new, q_new)
+    _check_kv(shape, k_cache, "k_cache")
+    _check_kv(shape, v_cache, "v_cache")
+    _check_q(shape, q_cache)
+    kv = (shape.num_problems, shape.kv_heads, shape.head_dim)
+    qs = (shape.num_problems, shape.q_heads, shape.head_dim)
+    for t, want in ((k_new, kv), (v_new, kv), (q_new, qs)):
+        if tuple(t.shape) != want or t.dtype != torch.bfloat16 or not t.is_contiguous():
+            raise ValueError(f"new rows must be contiguous bf16 {want}")
+    prm = shape.params(k_cache, v_cache)
+    s = load_library().rkv_cache_append(ctypes.byref(prm), _ptr(k_cache), _ptr(v_cache), _ptr(q_cache), _ptr(k_new),
+                                        _ptr(v_new), _ptr(q_new), int(position), int(q_slot), _stream())
+    if s != RKV_OK:
+        raise RkvError(s, "rkv_cache_append")
 
 
 def rkv_workspace_size(shape: Shape) -> int:
@@ -217,7 +260,8 @@ def rkv_compact(shape: Shape, k: torch.Tensor, v: torch.Tensor, kept_idx: torch.
         k_out = torch.empty(oshape, dtype=torch.bfloat16, device=k.device)
     if v_out is None:
         v_out = torch.empty(oshape, dtype=torch.bfloat16, device=k.device)
-    prm = shape.params(k, v)
+    _check_out(shape, k_out, v_out)
+    prm = shape.params(k, v, k_out)
     s = load_library().rkv_compact(ctypes.byref(prm), _ptr(k), _ptr(v), _ptr(kept_idx), _ptr(k_out), _ptr(v_out),
                                    _stream())
     if s != RKV_OK:
@@ -248,7 +292,8 @@ def rkv_compress(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Te
     if score is None and want_score:
         score = torch.empty((shape.num_problems, shape.kv_heads, shape.n_cand), dtype=torch.float32, device=dev)
     ws, wp, wb = _ws_args(shape, ws, dev)
-    prm = shape.params(k, v)
+    _check_out(shape, k_out, v_out)
+    prm = shape.params(k, v, k_out)
     lib = load_library()
     if events is None:
         s = lib.rkv_compress(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out),

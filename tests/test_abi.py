@@ -25,15 +25,15 @@ def declared_symbols(repo_root):
 
 def test_every_declared_symbol_is_exported(lib, repo_root):
     names = declared_symbols(repo_root)
-    assert names == ["rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_score_importance", "rkv_score_redundancy",
-                     "rkv_select_topk", "rkv_status_string", "rkv_workspace_size"]
+    assert names == ["rkv_cache_append", "rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_score_importance", "rkv_score_redundancy",
+                     "rkv_select_topk", "rkv_should_compress", "rkv_status_string", "rkv_workspace_size"]
     for n in names:
         assert hasattr(lib, n), n
     assert set(rkv.__dict__) >= set(names) - {"rkv_status_string", "rkv_compress_events"}
 
 
 def test_params_struct_layout_matches_header():
-    assert ctypes.sizeof(rkv.RkvParams) == 13 * 4 + 4 + 6 * 8      # 13 32-bit fields, pad to 8, 6 strides
+    assert ctypes.sizeof(rkv.RkvParams) == 13 * 4 + 4 + 9 * 8      # 13 32-bit fields, pad to 8, 9 strides
     assert rkv.RkvParams.k_stride_problem.offset == 56
 
 
@@ -102,3 +102,17 @@ def test_binding_refuses_cpu_tensors():
     q = torch.zeros((1, 4, 8, 128), dtype=torch.bfloat16)
     with pytest.raises(RuntimeError, match="no CPU path"):
         rkv.rkv_compress(s, q, k, k)
+
+
+def test_trigger_rule(lib):
+    """Alg. 1: nothing happens until the rows held beyond the budget fill the buffer."""
+    p = shape(n_tokens=1152, budget=1024).params()
+    for held, want in [(0, rkv.RKV_NOT_TRIGGERED), (1024, rkv.RKV_NOT_TRIGGERED), (1151, rkv.RKV_NOT_TRIGGERED),
+                       (1152, rkv.RKV_OK)]:
+        assert lib.rkv_should_compress(ctypes.byref(p), held) == want
+    p2 = shape(n_tokens=1024, budget=1024).params()
+    assert lib.rkv_should_compress(ctypes.byref(p2), 1024) == rkv.RKV_NOT_TRIGGERED
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.rkv_cache_append(ctypes.byref(p), fake, fake, fake, fake, fake, fake, 1152, 0, None) == rkv.RKV_ERR_SHAPE
+    assert lib.rkv_cache_append(ctypes.byref(p), fake, fake, fake, fake, fake, fake, 0, 8, None) == rkv.RKV_ERR_SHAPE
+    assert lib.rkv_cache_append(ctypes.byref(p), None, fake, fake, fake, fake, fake, 0, 0, None) == rkv.RKV_ERR_NULL

@@ -431,3 +431,58 @@ def test_largest_supported_cache_sampled_rows():
     r = red[0, 0].cpu().numpy().astype(np.float64)
     assert abs(r.sum() - 1.0) < 1e-4                      # softmax over the candidates (Eq. 6)
     np.testing.assert_allclose(r, np.exp(msim[0, 0].cpu().numpy().astype(np.float64) - np.log(np.exp(msim[0, 0].cpu().numpy().astype(np.float64)).sum())), rtol=1e-4)
+
+
+# ------------------------------------------------------------------------------ decode loop
+def test_decode_loop_bookkeeping_and_per_event_parity():
+    """A synthetic decode run through DecodeCache: appended rows land where they should, the step
+    triggers every B_buffer tokens once the cache is full, and every compression event matches the
+    oracle run on the cache contents the GPU held at that moment."""
+    from paper_2505_24133_amd.decode import DecodeCache
+    P, H, G, alpha, budget, buffer = 2, 2, 4, 8, 96, 32
+    N = budget + buffer
+    shp = rkv.Shape(num_problems=P, kv_heads=H, q_heads=H * G, n_tokens=N, budget=budget, alpha=alpha,
+                    pool_w=2, beta=1, sim_threshold=0.5, lam=0.1)
+    w = synth.Workload("loop", P, H, H * G, N, budget, alpha=alpha, pool_w=2, beta=1, sim_threshold=0.5, lam=0.1)
+    prm = Hp.oracle_params(w)
+    cache = DecodeCache(shp)
+    rng = np.random.default_rng(5)
+    steps = N + 3 * buffer + 5
+    history_k = []
+    events = 0
+    for t in range(steps):
+        kf = rng.standard_normal((P, H, 128)).astype(np.float32)
+        if t > 10 and t % 3 == 0:                       # repetitive "reasoning": re-emit an earlier key, noisily
+            kf = history_k[int(rng.integers(0, t))] + 0.05 * rng.standard_normal((P, H, 128)).astype(np.float32)
+        history_k.append(kf)
+        vf = rng.standard_normal((P, H, 128)).astype(np.float32)
+        qf = rng.standard_normal((P, H * G, 128)).astype(np.float32)
+        kb, vb, qb = synth.f32_to_bf16_bits(kf), synth.f32_to_bf16_bits(vf), synth.f32_to_bf16_bits(qf)
+        will_fire = cache.length + 1 == N
+        before_k = host_bits(cache.k) if will_fire else None
+        before_v = host_bits(cache.v) if will_fire else None
+        pos = cache.length
+        say(f"decode step {t}: length {cache.length}{' -> compress' if will_fire else ''}")
+        fired = cache.append(dev_bf16(kb), dev_bf16(vb), dev_bf16(qb))
+        torch.cuda.synchronize()
+        assert fired == will_fire
+        if not fired:
+            np.testing.assert_array_equal(host_bits(cache.k)[:, :, pos], kb)
+            np.testing.assert_array_equal(host_bits(cache.v)[:, :, pos], vb)
+            assert cache.length == pos + 1
+        else:
+            events += 1
+            before_k[:, :, pos] = kb
+            before_v[:, :, pos] = vb
+            q_now = host_bits(cache.q_cache)
+            np.testing.assert_array_equal(q_now[:, :, t % alpha], qb)      # newest query is in its slot
+            kept = cache.kept_idx.cpu().numpy()
+            after_k, after_v = host_bits(cache.k), host_bits(cache.v)
+            assert cache.length == budget
+            for p in range(P):
+                for h in range(H):
+                    ref = O.compress_head(q_now[p, h * G:(h + 1) * G], before_k[p, h], before_v[p, h], prm)
+                    check_head(w, ref, None, kept[p, h], after_k[p, h, :budget], after_v[p, h, :budget],
+                               before_k[p, h], before_v[p, h], f"event{events}[p{p},h{h}]")
+    assert events == cache.compressions == 1 + 3
+    assert cache.tokens_seen == steps and cache.length == budget + 5
