@@ -129,6 +129,10 @@ ADVERSARIAL = [
     (577, 320, 3, 2, 8, 4, 4, 0.0, 1.0),      # T = 0: every positive similarity is a hit; lambda = 1
     (65, 17, 2, 4, 8, 4, 1, 0.5, 0.1),        # smaller than one tile
     (1030, 999, 1, 4, 8, 16, 3, 0.8, 0.05),   # wide pooling window
+    (300, 200, 1, 1, 64, 3, 1, 0.5, 0.1),     # alpha = 64, the largest observation window (MHA)
+    (390, 257, 1, 2, 32, 0, 64, 0.4, 0.2),    # G * alpha = 64 rows, beta larger than any hit count
+    (700, 650, 1, 4, 8, 400, 1, 0.5, 0.3),    # pooling window wider than the cache
+    (2100, 1900, 1, 4, 8, 4, 2, 0.5, 0.1),    # more than one staging block in the pooling stage
 ]
 
 
@@ -486,3 +490,33 @@ def test_decode_loop_bookkeeping_and_per_event_parity():
                                before_k[p, h], before_v[p, h], f"event{events}[p{p},h{h}]")
     assert events == cache.compressions == 1 + 3
     assert cache.tokens_seen == steps and cache.length == budget + 5
+
+
+def test_shared_workspace_across_shapes():
+    """One oversized workspace reused by calls of different shapes: nothing read is left over from
+    an earlier call."""
+    big = synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=2)
+    small = synth.Workload("small", 1, 2, 8, 203, 120, seed=5, recipe="rowcopy", redundancy=0.3, copy_noise=0.1)
+    ws = rkv.make_workspace(shape_of(big, 2))
+    ref = {}
+    for w in (big, small):
+        q, k, v = synth.make_batch(w)
+        ref[w.name] = (dev_bf16(q), dev_bf16(k), dev_bf16(v))
+    outs = {}
+    say("shared workspace: big, small, big, small")
+    for rnd in range(2):
+        for w in (big, small):
+            qd, kd, vd = ref[w.name]
+            o = rkv.rkv_compress(shape_of(w, w.num_problems), qd, kd, vd, ws=ws, want_score=True)
+            torch.cuda.synchronize()
+            if w.name in outs:
+                for x, y in zip(outs[w.name][1:], o[1:]):
+                    assert torch.equal(x, y)
+            outs[w.name] = tuple(t.clone() if isinstance(t, torch.Tensor) else t for t in o)
+    # and both agree with a call that owns a fresh workspace
+    for w in (big, small):
+        qd, kd, vd = ref[w.name]
+        o = rkv.rkv_compress(shape_of(w, w.num_problems), qd, kd, vd, want_score=True)
+        torch.cuda.synchronize()
+        for x, y in zip(outs[w.name][1:], o[1:]):
+            assert torch.equal(x, y)
