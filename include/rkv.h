@@ -55,6 +55,18 @@ typedef enum {
  * are bit-identical to flags = 0; only the amount of matrix work differs (data dependent).
  */
 #define RKV_FLAG_SKIP_SATURATED 1u
+/*
+ * Two variants that follow the paper's pseudo-code (Alg. 1) where it differs from the equations.
+ * RKV_FLAG_POOL_AFTER_MEAN: the attention weights are averaged over the alpha query rows first and the
+ * 2W-wide sliding max is applied to that average (default, Eq. 4: pool every row, then average).
+ * Needs (alpha + 1) * 2W <= 16384.
+ * RKV_FLAG_SHARED_SELECTION: the per-head scores Z are averaged over the H KV heads of a problem and
+ * the budget - alpha candidates with the largest average are kept in every head (default, Sec. 3.4:
+ * each head selects by its own Z).  kept_idx[p, h, :] is then the same list for every h; `score`
+ * still receives the per-head Z.  Applies to rkv_select_topk and rkv_compress.
+ */
+#define RKV_FLAG_POOL_AFTER_MEAN 2u
+#define RKV_FLAG_SHARED_SELECTION 4u
 
 typedef struct {
   int32_t num_problems;      /* P >= 0; an empty batch is valid and enqueues nothing */

@@ -41,6 +41,8 @@ class Params:
     sim_threshold: float = 0.5   # T
     lam: float = 0.1         # lambda
     eps: float = 1e-8
+    pool_after_mean: bool = False    # pseudo-code order: mean over the alpha rows, then the pooling
+    shared_selection: bool = False   # pseudo-code: scores averaged over the KV heads, one index set
 
 
 # ----------------------------------------------------------------------------- decode
@@ -90,6 +92,13 @@ def stabilise(A: np.ndarray, W: int) -> np.ndarray:
 def importance(q: np.ndarray, k_cand: np.ndarray, W: int) -> np.ndarray:
     """Eq. 4: I[i] = mean over the alpha query rows of the stabilised attention."""
     return stabilise(attention_weights(q, k_cand), W).mean(axis=0)
+
+
+def importance_mean_then_pool(q: np.ndarray, k_cand: np.ndarray, W: int) -> np.ndarray:
+    """The order of the paper's pseudo-code (Alg. 1): I'[k] = mean over the alpha query rows of A[:, k],
+    then the same 2W-wide sliding max applied to I'."""
+    mean = attention_weights(q, k_cand).mean(axis=0, keepdims=True)
+    return stabilise(mean, W)[0]
 
 
 # ------------------------------------------------------------------------- redundancy
@@ -174,7 +183,7 @@ def compress_head(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, pr
     k_sel = prm.budget - prm.alpha
     q = decode_bf16(q_bits)
     k_cand = decode_bf16(k_bits[:n])
-    I = importance(q, k_cand, prm.pool_w)
+    I = (importance_mean_then_pool if prm.pool_after_mean else importance)(q, k_cand, prm.pool_w)
     sbar = mean_similarity(k_cand, float(np.float32(prm.sim_threshold)), prm.beta, prm.eps)
     R = softmax_rows(sbar[None, :])[0]
     Z = selection_score(I, R, float(np.float32(prm.lam)))
@@ -182,6 +191,27 @@ def compress_head(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, pr
     kept = np.concatenate([keep, np.arange(n, N, dtype=np.int64)])
     return dict(importance=I, mean_sim=sbar, redundancy=R, score=Z, kept=kept,
                 k_out=k_bits[kept].copy(), v_out=v_bits[kept].copy())
+
+
+def compress_problem(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, prm: Params):
+    """One (sequence, layer) problem: q_bits [Hq, alpha, d], k_bits / v_bits [H, N, d].  Returns the list
+    of per-head dicts of ``compress_head``.  With ``prm.shared_selection`` the selection follows the
+    paper's pseudo-code: the per-head scores are averaged over the H heads and the k candidates with the
+    largest average are kept in every head (each dict then also holds ``shared_score``)."""
+    H, N = k_bits.shape[:2]
+    G = q_bits.shape[0] // H
+    heads = [compress_head(q_bits[h * G:(h + 1) * G], k_bits[h], v_bits[h], prm) for h in range(H)]
+    if prm.shared_selection:
+        n = N - prm.alpha
+        zbar = np.mean(np.stack([hd["score"] for hd in heads]), axis=0)
+        keep = select_topk(zbar, prm.budget - prm.alpha)
+        kept = np.concatenate([keep, np.arange(n, N, dtype=np.int64)])
+        for h, hd in enumerate(heads):
+            hd["shared_score"] = zbar
+            hd["kept"] = kept
+            hd["k_out"] = k_bits[h][kept].copy()
+            hd["v_out"] = v_bits[h][kept].copy()
+    return heads
 
 
 def compress(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, prm: Params, heads=None):

@@ -6,6 +6,8 @@
 
 namespace rkv {
 
+static constexpr uint32_t kKnownFlags = RKV_FLAG_SKIP_SATURATED | RKV_FLAG_POOL_AFTER_MEAN | RKV_FLAG_SHARED_SELECTION;
+
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 rkv_status make_plan(const rkv_params* prm, Plan* pl) {
@@ -15,19 +17,22 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
     return RKV_ERR_SHAPE;
   if (q.q_heads % q.kv_heads != 0) return RKV_ERR_SHAPE;
   if (q.n_tokens <= q.alpha || q.budget <= q.alpha) return RKV_ERR_SHAPE;
-  if (q.head_dim != kHeadDim || (q.flags & ~(uint32_t)RKV_FLAG_SKIP_SATURATED) != 0) return RKV_ERR_UNSUPPORTED;
+  if (q.head_dim != kHeadDim || (q.flags & ~kKnownFlags) != 0) return RKV_ERR_UNSUPPORTED;
   const int G = q.q_heads / q.kv_heads;
   if (q.alpha > kMaxQRows || (int64_t)G * q.alpha > kMaxQRows || q.n_tokens > 32768) return RKV_ERR_UNSUPPORTED;
   if ((int64_t)q.num_problems * q.kv_heads > (1 << 22)) return RKV_ERR_UNSUPPORTED;
   if (!(q.lambda >= 0.f && q.lambda <= 1.f) || !(q.sim_threshold >= 0.f && q.sim_threshold <= 1.f) ||
       !(q.eps >= 0.f) || !isfinite(q.eps) || q.beta < 0 || q.pool_w < 0)
     return RKV_ERR_PARAM;
-  if ((int64_t)q.alpha * (q.pool_w > 0 ? 2 * (int64_t)q.pool_w : 1) > 16384 || q.pool_w > 1000) return RKV_ERR_UNSUPPORTED;
+  const int64_t pool_rows = q.alpha + ((q.flags & RKV_FLAG_POOL_AFTER_MEAN) ? 1 : 0);
+  if (pool_rows * (q.pool_w > 0 ? 2 * (int64_t)q.pool_w : 1) > 16384 || q.pool_w > 1000) return RKV_ERR_UNSUPPORTED;
 
   pl->P = q.num_problems; pl->H = q.kv_heads; pl->G = G; pl->N = q.n_tokens; pl->alpha = q.alpha;
   pl->n = q.n_tokens - q.alpha; pl->budget = q.budget; pl->k_sel = q.budget - q.alpha;
   pl->W = q.pool_w; pl->beta = q.beta; pl->T = q.sim_threshold; pl->lambda = q.lambda; pl->eps = q.eps;
   pl->skip_saturated = (q.flags & RKV_FLAG_SKIP_SATURATED) != 0;
+  pl->pool_after_mean = (q.flags & RKV_FLAG_POOL_AFTER_MEAN) != 0;
+  pl->shared_selection = (q.flags & RKV_FLAG_SHARED_SELECTION) != 0;
   pl->heads = q.num_problems * q.kv_heads;
   pl->chunks = (pl->n + kChunk - 1) / kChunk;
   pl->n_pad = pl->chunks * kChunk;
@@ -61,7 +66,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->off_sbar = take(heads * np * 4);
   pl->off_imp = take(heads * np * 4);
   pl->off_red = take(heads * np * 4);
-  pl->off_keys = take(heads * np * 4);
+  pl->off_z = take(heads * np * 4);
   pl->off_idx = take(heads * (size_t)pl->budget * 4);
   pl->total = off;
   return RKV_OK;
@@ -133,8 +138,15 @@ rkv_status rkv_select_topk(const rkv_params* prm, const float* importance, const
   if (importance == nullptr || redundancy == nullptr || kept_idx == nullptr) return RKV_ERR_NULL;
   if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
   if (pl.N <= pl.budget) return RKV_NOT_TRIGGERED;
-  return hip_status(launch_finalize(pl, kModeSelect, static_cast<char*>(ws), importance, redundancy, nullptr,
-                                    nullptr, nullptr, score, kept_idx, static_cast<hipStream_t>(stream)));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* w = static_cast<char*>(ws);
+  if (!pl.shared_selection)
+    return hip_status(launch_finalize(pl, kModeSelect, w, importance, redundancy, nullptr, nullptr, nullptr, score,
+                                      kept_idx, st));
+  if ((s = hip_status(launch_finalize(pl, kModeScore, w, importance, redundancy, nullptr, nullptr, nullptr, score,
+                                      nullptr, st))) != RKV_OK)
+    return s;
+  return hip_status(launch_shared_select(pl, w, kept_idx, st));
 }
 
 rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, const int32_t* kept_idx,
@@ -172,9 +184,11 @@ static rkv_status compress_impl(const rkv_params* prm, const void* q_obs, const 
   const bool attention_only = (pl.lambda == 1.0f);
   if (!attention_only && (s = hip_status(launch_gram(pl, k, w, st))) != RKV_OK) return s;
   if ((s = mark(2)) != RKV_OK) return s;
-  const int mode = attention_only ? (kModeImportance | kModeSelect) : (kModeImportance | kModeRedundancy | kModeSelect);
+  const int pick = pl.shared_selection ? kModeScore : kModeSelect;
+  const int mode = (attention_only ? kModeImportance : (kModeImportance | kModeRedundancy)) | pick;
   if ((s = hip_status(launch_finalize(pl, mode, w, nullptr, nullptr, nullptr, nullptr, nullptr, score, idx, st))) != RKV_OK)
     return s;
+  if (pl.shared_selection && (s = hip_status(launch_shared_select(pl, w, idx, st))) != RKV_OK) return s;
   if ((s = mark(3)) != RKV_OK) return s;
   if ((s = hip_status(launch_gather(pl, k, v, idx, k_out, v_out, st))) != RKV_OK) return s;
   return mark(4);

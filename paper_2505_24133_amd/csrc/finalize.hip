@@ -6,6 +6,9 @@
 //                select on order-preserving integer keys held in LDS, ties resolved towards the
 //                larger index, kept indices emitted in ascending order by a workgroup prefix scan,
 //                followed by the alpha observation rows (Sec. 3.1).
+// Two variants follow the paper's pseudo-code (Alg. 1) instead of Eq. 4 / Sec. 3.4: the importance
+// may be averaged over the query rows before the pooling, and the selection may be shared by the KV
+// heads of a problem (scores averaged over the heads, one workgroup per problem selects).
 #include <algorithm>
 
 #include "rkv_internal.h"
@@ -29,8 +32,10 @@ struct FinArgs {
   float* red_out;        // [heads][n] or nullptr
   float* sbar_out;       // [heads][n] or nullptr
   float* score_out;      // [heads][n] or nullptr
+  float* z_tmp;          // [heads][n_pad] scores for the shared selection, or nullptr
   int32_t* kept;         // [heads][budget]
-  int n, n_pad, chunks, alpha, W, k_sel, budget, pool_floats;
+  int n, n_pad, chunks, alpha, W, k_sel, budget, pool_floats, pool_rows;
+  int pool_after_mean;
   float lambda;
 };
 
@@ -90,6 +95,79 @@ __device__ __forceinline__ uint32_t order_key(float z) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+// Exact top-k of the n keys held in LDS (equal keys: larger index first).  The k_sel selected indices
+// are written in ascending order, followed by n .. n + alpha - 1, to `copies` output lists that lie
+// `copy_stride` ints apart.  All threads of the workgroup call this; `keys` must be complete (the
+// caller synchronises before the call).
+__device__ void select_and_emit(const uint32_t* keys, int n, int k_sel, int alpha, int32_t* out, int copies,
+                                int64_t copy_stride, uint32_t* hist, uint32_t* scan_buf, uint32_t* sel) {
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  // ---- radix select: key of the k-th largest score
+  uint32_t prefix = 0, known = 0, krem = (uint32_t)k_sel, n_equal = 0;
+#pragma unroll 1
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (t < 256) hist[t] = 0;
+    __syncthreads();
+    for (int i0 = 0; i0 < n; i0 += kFinThreads) {
+      const int i = i0 + t;
+      const uint32_t key = (i < n) ? keys[i] : 0u;
+      bool live = (i < n) && ((key & known) == prefix);
+      const uint32_t digit = (key >> shift) & 255u;
+      // scores of one head are often close: count the wave's most common digit with one atomic
+      const unsigned long long am = __ballot(live);
+      if (am != 0ull) {
+        const int first = __ffsll((long long)am) - 1;
+        const uint32_t d0 = __shfl(digit, first);
+        const unsigned long long same = __ballot(live && digit == d0);
+        if (lane == first) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+        live = live && (digit != d0);
+        if (live) atomicAdd(&hist[digit], 1u);
+      }
+    }
+    __syncthreads();
+    // the bin holding the krem-th largest: bins above it hold fewer than krem keys
+    uint32_t total = 0;
+    const uint32_t mine = (t < 256) ? hist[255 - t] : 0u;      // thread t <-> bin 255 - t
+    const uint32_t above = block_exclusive_scan(mine, scan_buf, &total);
+    if (t < 256 && above < krem && above + mine >= krem) {
+      sel[0] = 255u - (uint32_t)t;
+      sel[1] = above;
+      sel[2] = mine;
+    }
+    __syncthreads();
+    prefix |= sel[0] << shift;
+    known |= 255u << shift;
+    krem -= sel[1];
+    n_equal = sel[2];
+    __syncthreads();
+  }
+  // keys > prefix are all kept; of the n_equal keys == prefix the krem with the largest indices
+  const uint32_t skip_eq = n_equal - krem;
+  uint32_t run_gt = 0, run_eq = 0;
+  for (int i0 = 0; i0 < n; i0 += kFinThreads) {
+    const int i = i0 + t;
+    const uint32_t key = (i < n) ? keys[i] : 0u;
+    const uint32_t gt = (i < n && key > prefix) ? 1u : 0u;
+    const uint32_t eq = (i < n && key == prefix) ? 1u : 0u;
+    uint32_t total;
+    const uint32_t ex = block_exclusive_scan(gt | (eq << 16), scan_buf, &total);
+    const uint32_t gt_before = run_gt + (ex & 0xffffu);
+    const uint32_t eq_before = run_eq + (ex >> 16);
+    const bool keep = gt || (eq && eq_before >= skip_eq);
+    if (keep) {
+      const uint32_t pos = gt_before + (eq_before > skip_eq ? eq_before - skip_eq : 0u);
+      for (int c = 0; c < copies; ++c) out[c * copy_stride + pos] = i;
+    }
+    run_gt += total & 0xffffu;
+    run_eq += total >> 16;
+  }
+  for (int r = t; r < alpha; r += kFinThreads)
+    for (int c = 0; c < copies; ++c) out[c * copy_stride + k_sel + r] = n + r;
+}
+
+constexpr int kModeZ = kModeSelect | kModeScore;     // modes that form the joint score
+
 template <int MODE>
 __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   extern __shared__ uint32_t keys[];            // n_pad order-preserving keys (select mode) / pooling stage
@@ -142,7 +220,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
     float* pool = reinterpret_cast<float*>(keys);            // the key buffer is not in use yet
     const int win = (a.W > 0) ? 2 * a.W : 1;
     const int halo = win - 1;
-    const int block_cols = min(a.pool_floats / a.alpha, 2 * kFinThreads) - halo;    // >= 1 (checked on the host)
+    const int block_cols = min(a.pool_floats / a.pool_rows, 2 * kFinThreads) - halo;  // >= 1 (checked on the host)
     for (int cb = 0; cb < n; cb += block_cols) {
       const int cols = min(block_cols, n - cb);
       const int width = cols + halo;
@@ -169,6 +247,25 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
           }
       }
       __syncthreads();
+      if (a.pool_after_mean) {
+        // Alg. 1 order: the mean over the query rows of the attention weights first (one extra LDS
+        // row; columns outside [0, n) hold exp(-inf) = 0, which never wins a max over weights >= 0
+        // because every window holds its own column), then the sliding max of that row
+        float* avg = pool + a.alpha * width;
+        for (int c = t; c < width; c += kFinThreads) {
+          float s = 0.f;
+          for (int j = 0; j < a.alpha; ++j) s += __expf(pool[j * width + c] - gmax[j]) * ginv[j];
+          avg[c] = s;
+        }
+        __syncthreads();
+        for (int li = t; li < cols; li += kFinThreads) {
+          float m = avg[li];
+          for (int c = 1; c < win; ++c) m = fmaxf(m, avg[li + c]);
+          imp_dst[cb + li] = m;
+        }
+        __syncthreads();
+        continue;
+      }
       for (int li = t; li < cols; li += kFinThreads) {
         float imp = 0.f;
         // eight query rows at a time: their window reads are independent LDS loads
@@ -194,7 +291,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   // ---- per-candidate redundancy and joint score
   for (int i = t; i < n; i += kFinThreads) {
     float imp = 0.f, rd = 0.f;
-    if constexpr ((MODE & kModeSelect) != 0) {
+    if constexpr ((MODE & kModeZ) != 0) {
       if constexpr ((MODE & kModeImportance) != 0) imp = imp_dst[i];
       else imp = a.imp_in[(int64_t)head * n + i];
     }
@@ -203,79 +300,40 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
       rd = __expf(s - smax) * sinv;
       if (a.red_out) a.red_out[(int64_t)head * n + i] = rd;
       if (a.sbar_out) a.sbar_out[(int64_t)head * n + i] = s;
-    } else if constexpr ((MODE & kModeSelect) != 0) {
+    } else if constexpr ((MODE & kModeZ) != 0) {
       rd = a.red_in ? a.red_in[(int64_t)head * n + i] : 0.f;      // no redundancy input: attention-only score
     }
-    if constexpr ((MODE & kModeSelect) != 0) {
+    if constexpr ((MODE & kModeZ) != 0) {
       const float z = a.lambda * imp - (1.0f - a.lambda) * rd;
       if (a.score_out) a.score_out[(int64_t)head * n + i] = z;
-      keys[i] = order_key(z);
+      if constexpr ((MODE & kModeScore) != 0) a.z_tmp[(int64_t)head * a.n_pad + i] = z;
+      else keys[i] = order_key(z);
     }
   }
 
   if constexpr ((MODE & kModeSelect) != 0) {
-    // ---- radix select: key of the k-th largest score
-    uint32_t prefix = 0, known = 0, krem = (uint32_t)a.k_sel, n_equal = 0;
-#pragma unroll 1
-    for (int shift = 24; shift >= 0; shift -= 8) {
-      if (t < 256) hist[t] = 0;
-      __syncthreads();
-      for (int i0 = 0; i0 < n; i0 += kFinThreads) {
-        const int i = i0 + t;
-        const uint32_t key = (i < n) ? keys[i] : 0u;
-        bool live = (i < n) && ((key & known) == prefix);
-        const uint32_t digit = (key >> shift) & 255u;
-        // scores of one head are often close: count the wave's most common digit with one atomic
-        const unsigned long long am = __ballot(live);
-        if (am != 0ull) {
-          const int first = __ffsll((long long)am) - 1;
-          const uint32_t d0 = __shfl(digit, first);
-          const unsigned long long same = __ballot(live && digit == d0);
-          if (lane == first) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
-          live = live && (digit != d0);
-          if (live) atomicAdd(&hist[digit], 1u);
-        }
-      }
-      __syncthreads();
-      // the bin holding the krem-th largest: bins above it hold fewer than krem keys
-      uint32_t above = 0, total = 0;
-      const uint32_t mine = (t < 256) ? hist[255 - t] : 0u;      // thread t <-> bin 255 - t
-      above = block_exclusive_scan(mine, scan_buf, &total);
-      if (t < 256 && above < krem && above + mine >= krem) {
-        sel[0] = 255u - (uint32_t)t;
-        sel[1] = above;
-        sel[2] = mine;
-      }
-      __syncthreads();
-      prefix |= sel[0] << shift;
-      known |= 255u << shift;
-      krem -= sel[1];
-      n_equal = sel[2];
-      __syncthreads();
-    }
-    // keys > prefix are all kept; of the n_equal keys == prefix the krem with the largest indices
-    const uint32_t skip_eq = n_equal - krem;
-    int32_t* out = a.kept + (int64_t)head * a.budget;
-    uint32_t run_gt = 0, run_eq = 0;
-    for (int i0 = 0; i0 < n; i0 += kFinThreads) {
-      const int i = i0 + t;
-      const uint32_t key = (i < n) ? keys[i] : 0u;
-      const uint32_t gt = (i < n && key > prefix) ? 1u : 0u;
-      const uint32_t eq = (i < n && key == prefix) ? 1u : 0u;
-      uint32_t total;
-      const uint32_t ex = block_exclusive_scan(gt | (eq << 16), scan_buf, &total);
-      const uint32_t gt_before = run_gt + (ex & 0xffffu);
-      const uint32_t eq_before = run_eq + (ex >> 16);
-      const bool keep = gt || (eq && eq_before >= skip_eq);
-      if (keep) {
-        const uint32_t pos = gt_before + (eq_before > skip_eq ? eq_before - skip_eq : 0u);
-        out[pos] = i;
-      }
-      run_gt += total & 0xffffu;
-      run_eq += total >> 16;
-    }
-    for (int r = t; r < a.alpha; r += kFinThreads) out[a.k_sel + r] = n + r;
+    __syncthreads();
+    select_and_emit(keys, n, a.k_sel, a.alpha, a.kept + (int64_t)head * a.budget, 1, 0, hist, scan_buf, sel);
   }
+}
+
+// Shared selection (Alg. 1): one workgroup per problem averages the H per-head scores of each
+// candidate (fp32, heads in ascending order) and writes the one kept list into every head's slot.
+__global__ __launch_bounds__(kFinThreads) void shared_select_kernel(const float* z, int32_t* kept, int H, int n,
+                                                                    int n_pad, int k_sel, int alpha, int budget) {
+  extern __shared__ uint32_t keys[];
+  __shared__ uint32_t scan_buf[kFinWaves];
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sel[3];
+  const int p = blockIdx.x;
+  const float inv_h = 1.0f / (float)H;
+  for (int i = threadIdx.x; i < n; i += kFinThreads) {
+    float s = 0.f;
+    for (int h = 0; h < H; ++h) s += z[((int64_t)p * H + h) * n_pad + i];
+    keys[i] = order_key(s * inv_h);
+  }
+  __syncthreads();
+  select_and_emit(keys, n, k_sel, alpha, kept + (int64_t)p * H * budget, H, budget, hist, scan_buf, sel);
 }
 
 template <int MODE>
@@ -308,13 +366,16 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   a.k_sel = pl.k_sel; a.budget = pl.budget;
   a.lambda = pl.lambda;
   a.imp_tmp = reinterpret_cast<float*>(ws + pl.off_imp);
+  a.z_tmp = reinterpret_cast<float*>(ws + pl.off_z);
+  a.pool_after_mean = pl.pool_after_mean ? 1 : 0;
+  a.pool_rows = pl.alpha + a.pool_after_mean;
   // dynamic LDS: the select keys (n_pad words) and the pooling stage share one region
   size_t words = (mode & kModeSelect) ? (size_t)pl.n_pad : 0;
   a.pool_floats = 0;
   if (mode & kModeImportance) {
     const int win = pl.W > 0 ? 2 * pl.W : 1;
-    const size_t want = (size_t)pl.alpha * (size_t)(std::min(pl.n, 2048) + win - 1);
-    const size_t least = (size_t)pl.alpha * (size_t)win;          // one column per block at the very least
+    const size_t want = (size_t)a.pool_rows * (size_t)(std::min(pl.n, 2048) + win - 1);
+    const size_t least = (size_t)a.pool_rows * (size_t)win;       // one column per block at the very least
     size_t pool = std::min(std::max(want, least), (size_t)kMaxPoolFloats);
     if (pool < least) return hipErrorInvalidValue;                // rejected earlier by make_plan
     a.pool_floats = (int)pool;
@@ -329,8 +390,27 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
       return launch_mode<kModeImportance | kModeSelect>(a, pl.heads, lds, stream);
     case kModeImportance | kModeRedundancy | kModeSelect:
       return launch_mode<kModeImportance | kModeRedundancy | kModeSelect>(a, pl.heads, lds, stream);
+    case kModeScore: return launch_mode<kModeScore>(a, pl.heads, lds, stream);
+    case kModeImportance | kModeScore:
+      return launch_mode<kModeImportance | kModeScore>(a, pl.heads, lds, stream);
+    case kModeImportance | kModeRedundancy | kModeScore:
+      return launch_mode<kModeImportance | kModeRedundancy | kModeScore>(a, pl.heads, lds, stream);
     default: return hipErrorInvalidValue;
   }
+}
+
+hipError_t launch_shared_select(const Plan& pl, char* ws, int32_t* kept_idx, hipStream_t stream) {
+  static bool configured = false;
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shared_select_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(shared_select_kernel, dim3(pl.P), dim3(kFinThreads), (size_t)pl.n_pad * sizeof(uint32_t), stream,
+                     reinterpret_cast<const float*>(ws + pl.off_z), kept_idx, pl.H, pl.n, pl.n_pad, pl.k_sel,
+                     pl.alpha, pl.budget);
+  return hipGetLastError();
 }
 
 }  // namespace rkv

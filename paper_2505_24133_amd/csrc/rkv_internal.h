@@ -26,6 +26,8 @@ struct Plan {
   int n_pad;          // chunks * kChunk
   float T, lambda, eps;
   bool skip_saturated;     // RKV_FLAG_SKIP_SATURATED
+  bool pool_after_mean;    // RKV_FLAG_POOL_AFTER_MEAN
+  bool shared_selection;   // RKV_FLAG_SHARED_SELECTION
   int64_t ksp, ksh, kst;   // key strides (elements)
   int64_t vsp, vsh, vst;   // value strides (elements)
   int64_t osp, osh, ost;   // strides of the compacted outputs (elements)
@@ -36,7 +38,7 @@ struct Plan {
   size_t off_sbar;    // float [heads][n_pad]           mean similarity
   size_t off_imp;     // float [heads][n_pad]           importance (fused path)
   size_t off_red;     // float [heads][n_pad]           redundancy (fused path)
-  size_t off_keys;    // uint  [heads][n_pad]           order-preserving keys of Z
+  size_t off_z;       // float [heads][n_pad]           per-head scores Z (shared selection)
   size_t off_idx;     // int   [heads][budget]          kept indices when the caller passes none
   size_t total;
 };
@@ -50,12 +52,15 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
 enum SelectMode : int {
   kModeImportance = 1,   // workspace logits -> importance
   kModeRedundancy = 2,   // workspace mean similarity -> redundancy
-  kModeSelect = 4,       // importance, redundancy -> Z, kept indices
+  kModeSelect = 4,       // importance, redundancy -> Z, kept indices (per head)
+  kModeScore = 8,        // importance, redundancy -> Z in the workspace, no selection
 };
 hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
                            const float* imp_in, const float* red_in,
                            float* imp_out, float* red_out, float* sbar_out,
                            float* score_out, int32_t* kept_idx, hipStream_t stream);
+// One kept list per problem from the head-averaged workspace scores, replicated to every head.
+hipError_t launch_shared_select(const Plan& pl, char* ws, int32_t* kept_idx, hipStream_t stream);
 hipError_t launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* kept_idx,
                          void* k_out, void* v_out, hipStream_t stream);
 

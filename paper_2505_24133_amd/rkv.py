@@ -25,6 +25,8 @@ RKV_ERR_WORKSPACE = -4
 RKV_ERR_PARAM = -5
 RKV_ERR_HIP = -6
 RKV_FLAG_SKIP_SATURATED = 1
+RKV_FLAG_POOL_AFTER_MEAN = 2
+RKV_FLAG_SHARED_SELECTION = 4
 
 
 class RkvParams(ctypes.Structure):

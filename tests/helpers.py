@@ -13,9 +13,9 @@ ABS_TOL = 1e-5
 SIM_BAND = 1e-5
 
 
-def oracle_params(w) -> O.Params:
+def oracle_params(w, **variant) -> O.Params:
     return O.Params(alpha=w.alpha, budget=w.budget, pool_w=w.pool_w, beta=w.beta,
-                    sim_threshold=w.sim_threshold, lam=w.lam, eps=w.eps)
+                    sim_threshold=w.sim_threshold, lam=w.lam, eps=w.eps, **variant)
 
 
 def close(gpu: np.ndarray, ref: np.ndarray, rel=REL_TOL, abs_=ABS_TOL) -> np.ndarray:

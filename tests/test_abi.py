@@ -61,6 +61,11 @@ def test_workspace_size_and_validation(lib):
     assert ws_status(lib, shape(budget=8))[0] == rkv.RKV_ERR_SHAPE
     assert ws_status(lib, shape(n_tokens=8))[0] == rkv.RKV_ERR_SHAPE
     assert ws_status(lib, shape(head_dim=64))[0] == rkv.RKV_ERR_UNSUPPORTED
+    assert ws_status(lib, shape(flags=8))[0] == rkv.RKV_ERR_UNSUPPORTED            # unknown flag bit
+    assert ws_status(lib, shape(flags=7))[0] == rkv.RKV_OK                         # the three known ones
+    # pooling stage holds alpha rows, one more when the mean is taken before the pooling
+    assert ws_status(lib, shape(alpha=63, q_heads=8, pool_w=130))[0] == rkv.RKV_OK            # 63 * 260 <= 16384
+    assert ws_status(lib, shape(alpha=63, q_heads=8, pool_w=130, flags=2))[0] == rkv.RKV_ERR_UNSUPPORTED
     assert ws_status(lib, shape(q_heads=8 * 9))[0] == rkv.RKV_ERR_UNSUPPORTED     # G * alpha = 72 > 64
     assert ws_status(lib, shape(n_tokens=40000, budget=30000))[0] == rkv.RKV_ERR_UNSUPPORTED
     assert ws_status(lib, shape(lam=1.5))[0] == rkv.RKV_ERR_PARAM

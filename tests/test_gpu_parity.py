@@ -40,8 +40,12 @@ def shape_of(w: synth.Workload, P: int) -> rkv.Shape:
                      sim_threshold=w.sim_threshold, lam=w.lam, eps=w.eps)
 
 
-def check_head(w, ref, z_gpu, kept_gpu, kout, vout, kb, vb, tag, imp=None, red=None, msim=None):
-    """Compare one head's GPU results with the oracle's dict `ref`."""
+def check_head(w, ref, z_gpu, kept_gpu, kout, vout, kb, vb, tag, imp=None, red=None, msim=None,
+               z_select=None, frag_select=None):
+    """Compare one head's GPU results with the oracle's dict `ref`.  With the shared selection the
+    kept list is the top-k of `z_select` (the head mean of the GPU's scores, formed as the kernel
+    forms it) and is compared with the oracle's `shared_score`; `frag_select` marks the candidates
+    that are threshold-fragile in any head."""
     n, k = w.n_cand, w.k_sel
     kc = O.decode_bf16(kb[:n])
     frag = Hp.fragile_rows(kc, float(np.float32(w.sim_threshold)), w.beta, w.eps)
@@ -64,9 +68,11 @@ def check_head(w, ref, z_gpu, kept_gpu, kout, vout, kb, vb, tag, imp=None, red=N
         sel = kept_gpu[:k].astype(np.int64)
         assert np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] < n, f"{tag}: kept order/range"
         np.testing.assert_array_equal(kept_gpu[k:], np.arange(n, w.n_tokens), err_msg=f"{tag}: observation rows")
-        if z_gpu is not None:
-            np.testing.assert_array_equal(sel, Hp.exact_topk(z_gpu, k), err_msg=f"{tag}: not the top-k of its own score")
-        mk, md, free = Hp.check_kept_against_oracle(sel, ref["score"], k, frag)
+        own = z_select if z_select is not None else z_gpu
+        if own is not None:
+            np.testing.assert_array_equal(sel, Hp.exact_topk(own, k), err_msg=f"{tag}: not the top-k of its own score")
+        z_ref = ref["shared_score"] if z_select is not None else ref["score"]
+        mk, md, free = Hp.check_kept_against_oracle(sel, z_ref, k, frag if frag_select is None else frag_select)
         assert mk == 0 and md == 0, f"{tag}: kept set vs oracle: {mk} missing, {md} extra (free {free})"
         if kout is not None:
             np.testing.assert_array_equal(kout, kb[kept_gpu], err_msg=f"{tag}: K_out")
@@ -74,11 +80,23 @@ def check_head(w, ref, z_gpu, kept_gpu, kout, vout, kb, vb, tag, imp=None, red=N
     return int(frag.sum())
 
 
-def run_fused(w, q, k, v, heads, tag, check_parts=False):
+def head_mean_fp32(z):
+    """Mean over the heads of z [H, n] as the shared-selection kernel forms it: fp32 running sum over
+    ascending h, times fp32(1 / H)."""
+    s = np.zeros(z.shape[1], dtype=np.float32)
+    for h in range(z.shape[0]):
+        s = s + z[h].astype(np.float32)
+    return s * np.float32(1.0 / z.shape[0])
+
+
+def run_fused(w, q, k, v, heads, tag, check_parts=False, flags=0):
     """q,k,v: uint16 [P,...].  Runs rkv_compress (and optionally every stand-alone entry point) and
-    checks the listed (p, h) heads against the oracle."""
+    checks the listed (p, h) heads against the oracle.  With RKV_FLAG_SHARED_SELECTION every head of
+    the problems named in `heads` is checked."""
     P = k.shape[0]
     shp = shape_of(w, P)
+    shp.flags = flags
+    shared = bool(flags & rkv.RKV_FLAG_SHARED_SELECTION)
     say(f"{tag}: rkv_compress P={P} H={w.kv_heads} N={w.n_tokens} budget={w.budget} G={w.group} "
         f"alpha={w.alpha} W={w.pool_w} beta={w.beta} T={w.sim_threshold} lam={w.lam}")
     qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
@@ -98,9 +116,26 @@ def run_fused(w, q, k, v, heads, tag, check_parts=False):
         parts = (imp.cpu().numpy(), red.cpu().numpy(), msim.cpu().numpy())
     ko_h, vo_h = host_bits(ko), host_bits(vo)
     idx_h, score_h = idx.cpu().numpy(), score.cpu().numpy()
-    prm = Hp.oracle_params(w)
+    prm = Hp.oracle_params(w, pool_after_mean=bool(flags & rkv.RKV_FLAG_POOL_AFTER_MEAN), shared_selection=shared)
     G = w.group
     nfrag = 0
+    if shared:
+        n = w.n_cand
+        for p in sorted({p for (p, _) in heads}):
+            refs = O.compress_problem(q[p], k[p], v[p], prm)
+            frag_any = np.zeros(n, dtype=bool)
+            for h in range(w.kv_heads):
+                frag_any |= Hp.fragile_rows(O.decode_bf16(k[p, h, :n]), float(np.float32(w.sim_threshold)), w.beta, w.eps)
+            zbar = head_mean_fp32(score_h[p])
+            for h in range(w.kv_heads):
+                assert np.array_equal(idx_h[p, h], idx_h[p, 0]), f"{tag}[p{p}]: heads hold different kept lists"
+                extra = {}
+                if parts is not None:
+                    extra = dict(imp=parts[0][p, h], red=parts[1][p, h], msim=parts[2][p, h])
+                nfrag += check_head(w, refs[h], score_h[p, h], idx_h[p, h], ko_h[p, h], vo_h[p, h], k[p, h], v[p, h],
+                                    f"{tag}[p{p},h{h}]", z_select=zbar, frag_select=frag_any, **extra)
+        say(f"{tag}: shared selection matches ({nfrag} threshold-fragile rows exempt)")
+        return idx, score, ko, vo
     for (p, h) in heads:
         ref = O.compress_head(q[p, h * G:(h + 1) * G], k[p, h], v[p, h], prm)
         extra = {}
@@ -143,6 +178,41 @@ def test_adversarial_shapes(case):
                        lam=lam, seed=77 + N, recipe="rowcopy", redundancy=0.35, copy_noise=0.15)
     q, k, v = synth.make_batch(w)
     run_fused(w, q, k, v, [(p, h) for p in range(2) for h in range(H)], f"adv{N}", check_parts=True)
+
+
+VARIANT_SHAPES = [
+    # N, budget, kv_heads, G, alpha, W, beta, T, lam
+    (203, 120, 2, 4, 8, 4, 1, 0.5, 0.1),
+    (452, 300, 3, 5, 12, 7, 1, 0.6, 0.3),
+    (300, 200, 1, 1, 63, 3, 1, 0.5, 0.1),      # alpha + 1 = 64 rows in the pooling stage
+    (700, 650, 2, 4, 8, 400, 1, 0.5, 0.3),     # pooling window wider than the cache
+    (2100, 1900, 4, 2, 8, 4, 2, 0.5, 0.1),     # more than one staging block
+    (260, 250, 5, 1, 4, 0, 0, 0.5, 0.5),       # no pooling, five heads averaged
+]
+VARIANT_FLAGS = {"mean_then_pool": 2, "shared": 4, "both": 6}
+
+
+@pytest.mark.parametrize("variant", sorted(VARIANT_FLAGS))
+@pytest.mark.parametrize("case", VARIANT_SHAPES, ids=lambda c: f"N{c[0]}_H{c[2]}_G{c[3]}_a{c[4]}_W{c[5]}")
+def test_pseudo_code_variants(case, variant):
+    """The two places where the paper's pseudo-code differs from its equations: mean over the query
+    rows before the pooling, and one selection per problem from the head-averaged score."""
+    N, budget, H, G, alpha, W, beta, T, lam = case
+    flags = VARIANT_FLAGS[variant]
+    assert flags == {"mean_then_pool": rkv.RKV_FLAG_POOL_AFTER_MEAN, "shared": rkv.RKV_FLAG_SHARED_SELECTION,
+                     "both": rkv.RKV_FLAG_POOL_AFTER_MEAN | rkv.RKV_FLAG_SHARED_SELECTION}[variant]
+    w = synth.Workload("var", 2, H, H * G, N, budget, alpha=alpha, pool_w=W, beta=beta, sim_threshold=T,
+                       lam=lam, seed=500 + N, recipe="rowcopy", redundancy=0.35, copy_noise=0.15)
+    q, k, v = synth.make_batch(w)
+    run_fused(w, q, k, v, [(p, h) for p in range(2) for h in range(H)], f"{variant}{N}", check_parts=True, flags=flags)
+
+
+def test_pseudo_code_variants_cfg2_full_size():
+    """Both variants at the benchmark's launch shape; four problems (32 heads) against the oracle."""
+    w = synth.CONFIGS["cfg2_llama8b_b1024"]
+    q, k, v = synth.make_batch(w)
+    flags = rkv.RKV_FLAG_POOL_AFTER_MEAN | rkv.RKV_FLAG_SHARED_SELECTION
+    run_fused(w, q, k, v, [(p, 0) for p in (0, 9, 18, 31)], "cfg2_variants", flags=flags)
 
 
 def test_cfg2_llama8b_full_size_all_heads():

@@ -144,6 +144,49 @@ def test_importance_sums():
     np.testing.assert_allclose(O.stabilise(A, 0).mean(0)[[2, 7]], 0.5)
 
 
+def test_golden_pool_order_and_mean_then_pool_variant():
+    g = read_golden("pool_order_two_rows.txt")
+    A = np.stack([g["A_row0"], g["A_row1"]])
+    np.testing.assert_allclose(O.stabilise(A, 1).mean(0), g["pool_then_mean"], rtol=1e-14)
+    np.testing.assert_allclose(O.stabilise(A.mean(0, keepdims=True), 1)[0], g["mean_then_pool"], rtol=1e-14)
+    # the variant function against the library max-pool of the mean, and the ordering inequality
+    rng = np.random.default_rng(41)
+    q = rng.standard_normal((3, 5, 16))
+    k = rng.standard_normal((60, 16))
+    for W in (0, 1, 3, 6):
+        got = O.importance_mean_then_pool(q, k, W)
+        mean = torch.from_numpy(O.attention_weights(q, k).mean(0))[None, None]
+        if W == 0:
+            ref = mean[0, 0].numpy()
+        else:
+            ref = torch.nn.functional.max_pool1d(torch.nn.functional.pad(mean, (W, W - 1), value=-math.inf),
+                                                 kernel_size=2 * W, stride=1)[0, 0].numpy()
+        np.testing.assert_allclose(got, ref, rtol=1e-13)
+        assert np.all(got <= O.importance(q, k, W) + 1e-15)       # max of the mean <= mean of the maxes
+    assert abs(O.importance_mean_then_pool(q, k, 0).sum() - 1.0) < 1e-12
+
+
+def test_shared_selection_is_topk_of_the_head_mean():
+    w = synth.scaled(synth.CONFIGS["cfg1_tiny"], n_tokens=80, budget=40, kv_heads=3, q_heads=6)
+    q, k, v = synth.make_batch(w)
+    base = O.Params(alpha=w.alpha, budget=w.budget, pool_w=2, lam=0.1)
+    shared = O.Params(alpha=w.alpha, budget=w.budget, pool_w=2, lam=0.1, shared_selection=True)
+    per_head = O.compress_problem(q[0], k[0], v[0], base)
+    sh = O.compress_problem(q[0], k[0], v[0], shared)
+    n, ksel = w.n_cand, w.k_sel
+    zbar = sum(hd["score"] for hd in per_head) / 3.0
+    order = sorted(range(n), key=lambda i: (-zbar[i], -i))[:ksel]
+    for h in range(3):
+        np.testing.assert_allclose(sh[h]["score"], per_head[h]["score"], rtol=0)      # scores are unchanged
+        assert sh[h]["kept"][:ksel].tolist() == sorted(order)
+        np.testing.assert_array_equal(sh[h]["kept"][ksel:], np.arange(n, w.n_tokens))
+        np.testing.assert_array_equal(sh[h]["k_out"], k[0, h][sh[h]["kept"]])
+    np.testing.assert_allclose(sh[0]["shared_score"], zbar, rtol=1e-14)
+    # with a single head the shared selection is the per-head selection
+    one = O.compress_problem(q[0][:2], k[0][:1], v[0][:1], shared)
+    np.testing.assert_array_equal(one[0]["kept"], per_head[0]["kept"])
+
+
 # --------------------------------------------------------------------- cosine (Eq. 5)
 def test_cosine_brute_force_and_library():
     rng = np.random.default_rng(6)
