@@ -67,6 +67,16 @@ typedef enum {
  */
 #define RKV_FLAG_POOL_AFTER_MEAN 2u
 #define RKV_FLAG_SHARED_SELECTION 4u
+/*
+ * How the G query heads of a group are merged.  Default (Eq. 2-3 as printed): element-wise max of the raw
+ * scaled logits, then one softmax over the candidates.  App. A.2 describes the pooling as acting on
+ * attention scores: RKV_FLAG_GQA_SOFTMAX_THEN_MAX takes the softmax of every query head and then the max
+ * over the group (not renormalised), RKV_FLAG_GQA_SOFTMAX_THEN_MEAN the mean over the group (the pooling
+ * App. A.2 attributes to earlier work).  The two are mutually exclusive (RKV_ERR_PARAM); both make the
+ * workspace hold G * alpha instead of alpha logit rows per head.
+ */
+#define RKV_FLAG_GQA_SOFTMAX_THEN_MAX 8u
+#define RKV_FLAG_GQA_SOFTMAX_THEN_MEAN 16u
 
 typedef struct {
   int32_t num_problems;      /* P >= 0; an empty batch is valid and enqueues nothing */

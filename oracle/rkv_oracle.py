@@ -43,6 +43,7 @@ class Params:
     eps: float = 1e-8
     pool_after_mean: bool = False    # pseudo-code order: mean over the alpha rows, then the pooling
     shared_selection: bool = False   # pseudo-code: scores averaged over the KV heads, one index set
+    gqa: str = "max_logits"          # "max_logits" (Eq. 2-3) | "softmax_max" | "softmax_mean" (App. A.2)
 
 
 # ----------------------------------------------------------------------------- decode
@@ -65,16 +66,29 @@ def softmax_rows(x: np.ndarray) -> np.ndarray:
     return e / e.sum(axis=-1, keepdims=True)
 
 
-def attention_weights(q: np.ndarray, k_cand: np.ndarray) -> np.ndarray:
+def attention_weights(q: np.ndarray, k_cand: np.ndarray, gqa: str = "max_logits") -> np.ndarray:
     """Eq. 1 (G = 1) and Eq. 2-3 (G > 1).
 
     q [G, alpha, d] are the observation queries of the G query heads that share this
-    KV head, k_cand [n, d] the candidate keys.  Returns A [alpha, n], rows sum to 1.
+    KV head, k_cand [n, d] the candidate keys.  Returns A [alpha, n]; rows sum to 1 except with
+    "softmax_max".
+
+    ``gqa`` picks how the G heads are merged.  "max_logits" is Eq. 2-3 as printed: element-wise max
+    of the raw scaled logits, then one softmax.  App. A.2 instead speaks of pooling attention scores
+    (after the softmax), with the max adopted and the mean named as what earlier work used:
+    "softmax_max" = max over g of softmax(L^g) (not renormalised), "softmax_mean" = mean over g.
     """
     G, alpha, d = q.shape
     logits = np.stack([q[g] @ k_cand.T / np.sqrt(d) for g in range(G)])   # Eq. 2
-    pooled = logits.max(axis=0)                                           # max over the group
-    return softmax_rows(pooled)                                           # Eq. 3
+    if gqa == "max_logits":
+        pooled = logits.max(axis=0)                                       # max over the group
+        return softmax_rows(pooled)                                       # Eq. 3
+    per_head = np.stack([softmax_rows(logits[g]) for g in range(G)])      # Eq. 1 per query head
+    if gqa == "softmax_max":
+        return per_head.max(axis=0)
+    if gqa == "softmax_mean":
+        return per_head.mean(axis=0)
+    raise ValueError(gqa)
 
 
 def stabilise(A: np.ndarray, W: int) -> np.ndarray:
@@ -89,15 +103,15 @@ def stabilise(A: np.ndarray, W: int) -> np.ndarray:
     return out
 
 
-def importance(q: np.ndarray, k_cand: np.ndarray, W: int) -> np.ndarray:
+def importance(q: np.ndarray, k_cand: np.ndarray, W: int, gqa: str = "max_logits") -> np.ndarray:
     """Eq. 4: I[i] = mean over the alpha query rows of the stabilised attention."""
-    return stabilise(attention_weights(q, k_cand), W).mean(axis=0)
+    return stabilise(attention_weights(q, k_cand, gqa), W).mean(axis=0)
 
 
-def importance_mean_then_pool(q: np.ndarray, k_cand: np.ndarray, W: int) -> np.ndarray:
+def importance_mean_then_pool(q: np.ndarray, k_cand: np.ndarray, W: int, gqa: str = "max_logits") -> np.ndarray:
     """The order of the paper's pseudo-code (Alg. 1): I'[k] = mean over the alpha query rows of A[:, k],
     then the same 2W-wide sliding max applied to I'."""
-    mean = attention_weights(q, k_cand).mean(axis=0, keepdims=True)
+    mean = attention_weights(q, k_cand, gqa).mean(axis=0, keepdims=True)
     return stabilise(mean, W)[0]
 
 
@@ -183,7 +197,7 @@ def compress_head(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, pr
     k_sel = prm.budget - prm.alpha
     q = decode_bf16(q_bits)
     k_cand = decode_bf16(k_bits[:n])
-    I = (importance_mean_then_pool if prm.pool_after_mean else importance)(q, k_cand, prm.pool_w)
+    I = (importance_mean_then_pool if prm.pool_after_mean else importance)(q, k_cand, prm.pool_w, prm.gqa)
     sbar = mean_similarity(k_cand, float(np.float32(prm.sim_threshold)), prm.beta, prm.eps)
     R = softmax_rows(sbar[None, :])[0]
     Z = selection_score(I, R, float(np.float32(prm.lam)))

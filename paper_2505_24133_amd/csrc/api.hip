@@ -6,7 +6,9 @@
 
 namespace rkv {
 
-static constexpr uint32_t kKnownFlags = RKV_FLAG_SKIP_SATURATED | RKV_FLAG_POOL_AFTER_MEAN | RKV_FLAG_SHARED_SELECTION;
+static constexpr uint32_t kGqaFlags = RKV_FLAG_GQA_SOFTMAX_THEN_MAX | RKV_FLAG_GQA_SOFTMAX_THEN_MEAN;
+static constexpr uint32_t kKnownFlags =
+    RKV_FLAG_SKIP_SATURATED | RKV_FLAG_POOL_AFTER_MEAN | RKV_FLAG_SHARED_SELECTION | kGqaFlags;
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -22,7 +24,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   if (q.alpha > kMaxQRows || (int64_t)G * q.alpha > kMaxQRows || q.n_tokens > 32768) return RKV_ERR_UNSUPPORTED;
   if ((int64_t)q.num_problems * q.kv_heads > (1 << 22)) return RKV_ERR_UNSUPPORTED;
   if (!(q.lambda >= 0.f && q.lambda <= 1.f) || !(q.sim_threshold >= 0.f && q.sim_threshold <= 1.f) ||
-      !(q.eps >= 0.f) || !isfinite(q.eps) || q.beta < 0 || q.pool_w < 0)
+      !(q.eps >= 0.f) || !isfinite(q.eps) || q.beta < 0 || q.pool_w < 0 || (q.flags & kGqaFlags) == kGqaFlags)
     return RKV_ERR_PARAM;
   const int64_t pool_rows = q.alpha + ((q.flags & RKV_FLAG_POOL_AFTER_MEAN) ? 1 : 0);
   if (pool_rows * (q.pool_w > 0 ? 2 * (int64_t)q.pool_w : 1) > 16384 || q.pool_w > 1000) return RKV_ERR_UNSUPPORTED;
@@ -33,6 +35,8 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->skip_saturated = (q.flags & RKV_FLAG_SKIP_SATURATED) != 0;
   pl->pool_after_mean = (q.flags & RKV_FLAG_POOL_AFTER_MEAN) != 0;
   pl->shared_selection = (q.flags & RKV_FLAG_SHARED_SELECTION) != 0;
+  pl->gqa_mode = (q.flags & RKV_FLAG_GQA_SOFTMAX_THEN_MAX) ? 1 : ((q.flags & RKV_FLAG_GQA_SOFTMAX_THEN_MEAN) ? 2 : 0);
+  pl->qrows = (pl->gqa_mode == 0) ? q.alpha : G * q.alpha;
   pl->heads = q.num_problems * q.kv_heads;
   pl->chunks = (pl->n + kChunk - 1) / kChunk;
   pl->n_pad = pl->chunks * kChunk;
@@ -61,8 +65,8 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   auto take = [&](size_t bytes) { const size_t o = off; off = align_up(off + bytes); return o; };
   pl->off_rnorm = take(heads * np * 4);
   pl->off_upart = take(heads * pl->chunks * kHeadDim * 4);
-  pl->off_logit = take(heads * pl->alpha * np * 4);
-  pl->off_stats = take(heads * pl->chunks * pl->alpha * 2 * 4);
+  pl->off_logit = take(heads * pl->qrows * np * 4);
+  pl->off_stats = take(heads * pl->chunks * pl->qrows * 2 * 4);
   pl->off_sbar = take(heads * np * 4);
   pl->off_imp = take(heads * np * 4);
   pl->off_red = take(heads * np * 4);

@@ -22,8 +22,8 @@ constexpr int kFinWaves = kFinThreads / 64;
 constexpr int kMaxPoolFloats = 16384;           // 64 KB of LDS for the pooling stage
 
 struct FinArgs {
-  const float* logit;    // [heads][alpha][n_pad]
-  const float* stats;    // [heads][chunks][alpha][2]
+  const float* logit;    // [heads][rows][n_pad]
+  const float* stats;    // [heads][chunks][rows][2]
   const float* sbar;     // [heads][n_pad]
   const float* imp_in;   // [heads][n] (select-only mode)
   const float* red_in;   // [heads][n]
@@ -36,6 +36,7 @@ struct FinArgs {
   int32_t* kept;         // [heads][budget]
   int n, n_pad, chunks, alpha, W, k_sel, budget, pool_floats, pool_rows;
   int pool_after_mean;
+  int rows, G, group_mode;   // rows = logit rows per head: alpha, or G * alpha when group_mode != 0
   float lambda;
 };
 
@@ -181,23 +182,26 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   const int lane = t & 63;
   const int head = blockIdx.x;
   const int n = a.n;
-  const float* lg = a.logit + (int64_t)head * a.alpha * a.n_pad;
+  const float* lg = a.logit + (int64_t)head * a.rows * a.n_pad;
   const float* sb = a.sbar + (int64_t)head * a.n_pad;
 
   // ---- softmax denominators: one wave per query row, lanes over the chunks
   if constexpr ((MODE & kModeImportance) != 0) {
-    for (int j = t >> 6; j < a.alpha; j += kFinWaves) {
-      const float* st = a.stats + ((int64_t)head * a.chunks * a.alpha + j) * 2;
+    // the factor 1 / alpha of the mean over the query rows (and 1 / G of the mean over the group's
+    // heads, when that is how they are merged) is folded into the softmax normaliser
+    const float parts = (float)a.alpha * (a.group_mode == 2 ? (float)a.G : 1.0f);
+    for (int j = t >> 6; j < a.rows; j += kFinWaves) {
+      const float* st = a.stats + ((int64_t)head * a.chunks * a.rows + j) * 2;
       float m = -INFINITY;
-      for (int c = lane; c < a.chunks; c += 64) m = fmaxf(m, st[(int64_t)c * a.alpha * 2]);
+      for (int c = lane; c < a.chunks; c += 64) m = fmaxf(m, st[(int64_t)c * a.rows * 2]);
       m = wave_max(m);
       float den = 0.f;
       for (int c = lane; c < a.chunks; c += 64)
-        den += st[(int64_t)c * a.alpha * 2 + 1] * expf(st[(int64_t)c * a.alpha * 2] - m);
+        den += st[(int64_t)c * a.rows * 2 + 1] * expf(st[(int64_t)c * a.rows * 2] - m);
       den = wave_sum(den);
       if (lane == 0) {
         gmax[j] = m;
-        ginv[j] = 1.0f / (den * (float)a.alpha);
+        ginv[j] = 1.0f / (den * parts);
       }
     }
   }
@@ -225,6 +229,50 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
       const int cols = min(block_cols, n - cb);
       const int width = cols + halo;
       const int first = cb - a.W;                              // column held at pool[j][0]
+      if (a.group_mode != 0) {
+        // App. A.2 variants: the attention scores of every query head first (softmax per head), then
+        // the max or the mean over the G heads of the group; the staging buffer holds these scores
+        // (0 outside [0, n), which never wins a max over scores >= 0)
+        for (int j = 0; j < a.alpha; ++j)
+          for (int c = t; c < width; c += kFinThreads) {
+            const int col = first + c;
+            float pr = 0.f;
+            if (col >= 0 && col < n)
+              for (int g = 0; g < a.G; ++g) {
+                const int row = g * a.alpha + j;
+                const float x = __expf(lg[(int64_t)row * a.n_pad + col] - gmax[row]) * ginv[row];
+                pr = (a.group_mode == 1) ? fmaxf(pr, x) : pr + x;
+              }
+            pool[j * width + c] = pr;
+          }
+        __syncthreads();
+        if (a.pool_after_mean) {
+          float* avg = pool + a.alpha * width;
+          for (int c = t; c < width; c += kFinThreads) {
+            float s = 0.f;
+            for (int j = 0; j < a.alpha; ++j) s += pool[j * width + c];
+            avg[c] = s;
+          }
+          __syncthreads();
+          for (int li = t; li < cols; li += kFinThreads) {
+            float m = avg[li];
+            for (int c = 1; c < win; ++c) m = fmaxf(m, avg[li + c]);
+            imp_dst[cb + li] = m;
+          }
+        } else {
+          for (int li = t; li < cols; li += kFinThreads) {
+            float imp = 0.f;
+            for (int j = 0; j < a.alpha; ++j) {
+              float m = pool[j * width + li];
+              for (int c = 1; c < win; ++c) m = fmaxf(m, pool[j * width + li + c]);
+              imp += m;
+            }
+            imp_dst[cb + li] = imp;
+          }
+        }
+        __syncthreads();
+        continue;
+      }
       // four query rows x two column slots: eight independent loads per thread are in flight
       // before the first LDS store (width <= 2 * kFinThreads by the choice of block_cols)
       for (int j0 = 0; j0 < a.alpha; j0 += 4) {
@@ -368,6 +416,7 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   a.imp_tmp = reinterpret_cast<float*>(ws + pl.off_imp);
   a.z_tmp = reinterpret_cast<float*>(ws + pl.off_z);
   a.pool_after_mean = pl.pool_after_mean ? 1 : 0;
+  a.rows = pl.qrows; a.G = pl.G; a.group_mode = pl.gqa_mode;
   a.pool_rows = pl.alpha + a.pool_after_mean;
   // dynamic LDS: the select keys (n_pad words) and the pooling stage share one region
   size_t words = (mode & kModeSelect) ? (size_t)pl.n_pad : 0;

@@ -34,6 +34,7 @@ struct PrepassArgs {
   float* logit;
   float* stats;
   int H, G, alpha, n, n_pad, chunks, items;
+  int out_rows, out_groups;   // rows written per key: alpha (max over out_groups = G heads) or G*alpha (out_groups = 1)
   int64_t ksp, ksh, kst;
   float eps, scale;
 };
@@ -164,20 +165,21 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
         lg[qrow][wave * 32 + lrow] = acc[mt][i] * a.scale;
       }
     __syncthreads();
-    // ---- max over the G query heads of the group, per (query position j, key)
+    // ---- max over the G query heads of the group, per (query position j, key); when the heads are
+    // merged after their softmax (App. A.2) every head's row is written as it is (out_groups = 1)
     {
       const int key = t & (kChunk - 1);
       const bool valid = (j0 + key) < a.n;
-      for (int j = t >> 7; j < a.alpha; j += kPrepassThreads / kChunk) {
+      for (int j = t >> 7; j < a.out_rows; j += kPrepassThreads / kChunk) {
         float m = lg[j][key];
-        for (int g = 1; g < a.G; ++g) m = fmaxf(m, lg[g * a.alpha + j][key]);
-        if (valid) a.logit[((int64_t)head * a.alpha + j) * a.n_pad + j0 + key] = m;
+        for (int g = 1; g < a.out_groups; ++g) m = fmaxf(m, lg[g * a.out_rows + j][key]);
+        if (valid) a.logit[((int64_t)head * a.out_rows + j) * a.n_pad + j0 + key] = m;
         lg[j][key] = valid ? m : -INFINITY;      // row j (g = 0) is read by this thread only
       }
     }
     __syncthreads();
-    // ---- per-chunk softmax statistics for each query position
-    for (int j = wave; j < a.alpha; j += 4) {
+    // ---- per-chunk softmax statistics for each written row
+    for (int j = wave; j < a.out_rows; j += 4) {
       const float x0 = lg[j][lane], x1 = lg[j][lane + 64];
       float m = fmaxf(x0, x1);
 #pragma unroll
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
       if (lane == 0) {
-        float* st = a.stats + (((int64_t)head * a.chunks + chunk) * a.alpha + j) * 2;
+        float* st = a.stats + (((int64_t)head * a.chunks + chunk) * a.out_rows + j) * 2;
         st[0] = m;
         st[1] = s;
       }
@@ -211,6 +213,7 @@ hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char
   a.logit = reinterpret_cast<float*>(ws + pl.off_logit);
   a.stats = reinterpret_cast<float*>(ws + pl.off_stats);
   a.H = pl.H; a.G = pl.G; a.alpha = pl.alpha; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks;
+  a.out_rows = pl.qrows; a.out_groups = (pl.gqa_mode == 0) ? pl.G : 1;
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   a.eps = pl.eps;
   a.scale = 1.0f / sqrtf((float)kHeadDim);

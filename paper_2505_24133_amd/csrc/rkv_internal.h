@@ -28,13 +28,15 @@ struct Plan {
   bool skip_saturated;     // RKV_FLAG_SKIP_SATURATED
   bool pool_after_mean;    // RKV_FLAG_POOL_AFTER_MEAN
   bool shared_selection;   // RKV_FLAG_SHARED_SELECTION
+  int gqa_mode;            // 0: max of the logits, then softmax (Eq. 2-3); 1: softmax, then max; 2: softmax, then mean
+  int qrows;               // logit rows kept per head: alpha (mode 0) or G * alpha
   int64_t ksp, ksh, kst;   // key strides (elements)
   int64_t vsp, vsh, vst;   // value strides (elements)
   int64_t osp, osh, ost;   // strides of the compacted outputs (elements)
   size_t off_rnorm;   // float [heads][n_pad]           1 / (|K_i| + eps), 0 for i >= n
   size_t off_upart;   // float [heads][chunks][128]     per-chunk sums of r_i K_i
-  size_t off_logit;   // float [heads][alpha][n_pad]    group-max scaled logits
-  size_t off_stats;   // float [heads][chunks][alpha][2] per-chunk (max, sum exp)
+  size_t off_logit;   // float [heads][qrows][n_pad]    scaled logits (group max in mode 0)
+  size_t off_stats;   // float [heads][chunks][qrows][2] per-chunk (max, sum exp)
   size_t off_sbar;    // float [heads][n_pad]           mean similarity
   size_t off_imp;     // float [heads][n_pad]           importance (fused path)
   size_t off_red;     // float [heads][n_pad]           redundancy (fused path)

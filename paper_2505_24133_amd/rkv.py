@@ -27,6 +27,8 @@ RKV_ERR_HIP = -6
 RKV_FLAG_SKIP_SATURATED = 1
 RKV_FLAG_POOL_AFTER_MEAN = 2
 RKV_FLAG_SHARED_SELECTION = 4
+RKV_FLAG_GQA_SOFTMAX_THEN_MAX = 8
+RKV_FLAG_GQA_SOFTMAX_THEN_MEAN = 16
 
 
 class RkvParams(ctypes.Structure):

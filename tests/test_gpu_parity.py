@@ -116,7 +116,9 @@ def run_fused(w, q, k, v, heads, tag, check_parts=False, flags=0):
         parts = (imp.cpu().numpy(), red.cpu().numpy(), msim.cpu().numpy())
     ko_h, vo_h = host_bits(ko), host_bits(vo)
     idx_h, score_h = idx.cpu().numpy(), score.cpu().numpy()
-    prm = Hp.oracle_params(w, pool_after_mean=bool(flags & rkv.RKV_FLAG_POOL_AFTER_MEAN), shared_selection=shared)
+    gqa = ("softmax_max" if flags & rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MAX else
+           "softmax_mean" if flags & rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MEAN else "max_logits")
+    prm = Hp.oracle_params(w, pool_after_mean=bool(flags & rkv.RKV_FLAG_POOL_AFTER_MEAN), shared_selection=shared, gqa=gqa)
     G = w.group
     nfrag = 0
     if shared:
@@ -188,19 +190,22 @@ VARIANT_SHAPES = [
     (700, 650, 2, 4, 8, 400, 1, 0.5, 0.3),     # pooling window wider than the cache
     (2100, 1900, 4, 2, 8, 4, 2, 0.5, 0.1),     # more than one staging block
     (260, 250, 5, 1, 4, 0, 0, 0.5, 0.5),       # no pooling, five heads averaged
+    (390, 257, 2, 2, 32, 2, 1, 0.4, 0.2),      # G * alpha = 64 logit rows per head
 ]
-VARIANT_FLAGS = {"mean_then_pool": 2, "shared": 4, "both": 6}
+VARIANT_FLAGS = {"mean_then_pool": 2, "shared": 4, "both": 6, "gqa_softmax_max": 8, "gqa_softmax_mean": 16,
+                 "gqa_softmax_max_mean_then_pool_shared": 14, "gqa_softmax_mean_mean_then_pool": 18}
 
 
 @pytest.mark.parametrize("variant", sorted(VARIANT_FLAGS))
 @pytest.mark.parametrize("case", VARIANT_SHAPES, ids=lambda c: f"N{c[0]}_H{c[2]}_G{c[3]}_a{c[4]}_W{c[5]}")
 def test_pseudo_code_variants(case, variant):
-    """The two places where the paper's pseudo-code differs from its equations: mean over the query
-    rows before the pooling, and one selection per problem from the head-averaged score."""
+    """The places where the paper's pseudo-code or appendix differ from its equations: mean over the
+    query rows before the pooling, one selection per problem from the head-averaged score, and the
+    query heads of a group merged after their softmax (max or mean)."""
     N, budget, H, G, alpha, W, beta, T, lam = case
     flags = VARIANT_FLAGS[variant]
-    assert flags == {"mean_then_pool": rkv.RKV_FLAG_POOL_AFTER_MEAN, "shared": rkv.RKV_FLAG_SHARED_SELECTION,
-                     "both": rkv.RKV_FLAG_POOL_AFTER_MEAN | rkv.RKV_FLAG_SHARED_SELECTION}[variant]
+    assert (rkv.RKV_FLAG_POOL_AFTER_MEAN, rkv.RKV_FLAG_SHARED_SELECTION, rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MAX,
+            rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MEAN) == (2, 4, 8, 16)
     w = synth.Workload("var", 2, H, H * G, N, budget, alpha=alpha, pool_w=W, beta=beta, sim_threshold=T,
                        lam=lam, seed=500 + N, recipe="rowcopy", redundancy=0.35, copy_noise=0.15)
     q, k, v = synth.make_batch(w)
@@ -213,6 +218,10 @@ def test_pseudo_code_variants_cfg2_full_size():
     q, k, v = synth.make_batch(w)
     flags = rkv.RKV_FLAG_POOL_AFTER_MEAN | rkv.RKV_FLAG_SHARED_SELECTION
     run_fused(w, q, k, v, [(p, 0) for p in (0, 9, 18, 31)], "cfg2_variants", flags=flags)
+    run_fused(w, q, k, v, [(p, h) for p in (3, 30) for h in range(8)], "cfg2_gqa_softmax_max",
+              flags=rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MAX)
+    run_fused(w, q, k, v, [(p, h) for p in (5, 17) for h in range(8)], "cfg2_gqa_softmax_mean",
+              flags=rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MEAN)
 
 
 def test_cfg2_llama8b_full_size_all_heads():

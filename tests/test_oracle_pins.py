@@ -166,6 +166,43 @@ def test_golden_pool_order_and_mean_then_pool_variant():
     assert abs(O.importance_mean_then_pool(q, k, 0).sum() - 1.0) < 1e-12
 
 
+def test_golden_gqa_merge_variants_and_brute_force():
+    g = read_golden("gqa_merge_two_heads.txt")
+    # d = 2, keys = the two unit vectors: logit[g][0][i] = q[g][0][i] / sqrt(2)
+    q = math.sqrt(2.0) * np.stack([g["logits_head0"], g["logits_head1"]])[:, None, :]
+    k = np.eye(2)
+    for mode in ("max_logits", "softmax_max", "softmax_mean"):
+        np.testing.assert_allclose(O.attention_weights(q, k, mode)[0], g[mode], rtol=1e-14)
+    # brute force with explicit loops on random inputs
+    rng = np.random.default_rng(52)
+    G, alpha, n, d = 3, 4, 11, 8
+    q = rng.standard_normal((G, alpha, d))
+    k = rng.standard_normal((n, d))
+    P = np.zeros((G, alpha, n))
+    for gg in range(G):
+        for j in range(alpha):
+            e = [math.exp(sum(q[gg, j, c] * k[i, c] for c in range(d)) / math.sqrt(d)) for i in range(n)]
+            for i in range(n):
+                P[gg, j, i] = e[i] / sum(e)
+    for j in range(alpha):
+        for i in range(n):
+            assert abs(O.attention_weights(q, k, "softmax_max")[j, i] - max(P[gg, j, i] for gg in range(G))) < 1e-14
+            assert abs(O.attention_weights(q, k, "softmax_mean")[j, i] - sum(P[gg, j, i] for gg in range(G)) / G) < 1e-14
+    a_max, a_mean = O.attention_weights(q, k, "softmax_max"), O.attention_weights(q, k, "softmax_mean")
+    np.testing.assert_allclose(a_mean.sum(1), 1.0, rtol=1e-13)
+    assert np.all(a_max >= a_mean - 1e-16) and np.all(a_max.sum(1) <= G + 1e-12) and np.all(a_max.sum(1) >= 1 - 1e-12)
+    # one query head: all three are Eq. 1
+    ref = torch.softmax(torch.from_numpy(q[0]) @ torch.from_numpy(k).T / math.sqrt(d), dim=-1).numpy()
+    for mode in ("max_logits", "softmax_max", "softmax_mean"):
+        np.testing.assert_allclose(O.attention_weights(q[:1], k, mode), ref, rtol=1e-13)
+    # the mode reaches the importance and the compression step
+    for mode in ("softmax_max", "softmax_mean"):
+        np.testing.assert_allclose(O.importance(q, k, 2, mode), O.stabilise(O.attention_weights(q, k, mode), 2).mean(0), rtol=0)
+        assert not np.allclose(O.importance(q, k, 2, mode), O.importance(q, k, 2))
+    with pytest.raises(ValueError):
+        O.attention_weights(q, k, "median")
+
+
 def test_shared_selection_is_topk_of_the_head_mean():
     w = synth.scaled(synth.CONFIGS["cfg1_tiny"], n_tokens=80, budget=40, kv_heads=3, q_heads=6)
     q, k, v = synth.make_batch(w)
