@@ -138,6 +138,16 @@ rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, cons
                        void* k_out, void* v_out, void* stream);
 
 /*
+ * Compaction in place (Alg. 1 keeps one cache and sets its length to the budget): afterwards rows
+ * 0 .. budget-1 of k[p, h] and v[p, h] hold the rows kept_idx[p, h, :] selected; rows budget .. N-1 are
+ * left as they were.  kept_idx[P, H, budget] must be strictly ascending per head (as rkv_select_topk
+ * and rkv_compress write it), which makes every row move towards the front; a list that is not gives
+ * unspecified row contents (indices are still clamped into [0, N), nothing is accessed out of bounds).
+ * k, v use k_stride_* / v_stride_*; o_stride_* are ignored.  No workspace.
+ */
+rkv_status rkv_compact_inplace(const rkv_params* prm, void* k, void* v, const int32_t* kept_idx, void* stream);
+
+/*
  * The whole step (Sec. 3.1-3.4, Alg. 1): the four calls above back to back on `stream`
  * without host synchronisation.  kept_idx [P, H, budget] and score [P, H, n] are optional
  * outputs (NULL to skip).  Returns RKV_NOT_TRIGGERED without enqueuing anything when
@@ -147,6 +157,14 @@ rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, cons
 rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
                         void* k_out, void* v_out, int32_t* kept_idx, float* score,
                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * rkv_compress with the compaction of rkv_compact_inplace as its last stage: k and v are both the
+ * input cache [P, H, N, d] and, in their first `budget` rows, the output.  Same optional outputs,
+ * statuses and workspace as rkv_compress.
+ */
+rkv_status rkv_compress_inplace(const rkv_params* prm, const void* q_obs, void* k, void* v, int32_t* kept_idx,
+                                float* score, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Instrumented form of rkv_compress for measurement: identical work, and additionally records the

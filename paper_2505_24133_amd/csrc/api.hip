@@ -163,14 +163,25 @@ rkv_status rkv_compact(const rkv_params* prm, const void* k, const void* v, cons
   return hip_status(launch_gather(pl, k, v, kept_idx, k_out, v_out, static_cast<hipStream_t>(stream)));
 }
 
+rkv_status rkv_compact_inplace(const rkv_params* prm, void* k, void* v, const int32_t* kept_idx, void* stream) {
+  Plan pl;
+  const rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  if (empty(pl)) return RKV_OK;
+  if (k == nullptr || v == nullptr || kept_idx == nullptr) return RKV_ERR_NULL;
+  return hip_status(launch_compact_inplace(pl, k, v, kept_idx, static_cast<hipStream_t>(stream)));
+}
+
+// k_out == nullptr selects the in-place compaction of k and v.
 static rkv_status compress_impl(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
                                 void* k_out, void* v_out, int32_t* kept_idx, float* score,
-                                void* ws, size_t ws_bytes, void* stream, void* const* events) {
+                                void* ws, size_t ws_bytes, void* stream, void* const* events, bool inplace = false) {
   Plan pl;
   rkv_status s = make_plan(prm, &pl);
   if (s != RKV_OK) return s;
   if (empty(pl)) return RKV_OK;
-  if (q_obs == nullptr || k == nullptr || v == nullptr || k_out == nullptr || v_out == nullptr) return RKV_ERR_NULL;
+  if (q_obs == nullptr || k == nullptr || v == nullptr) return RKV_ERR_NULL;
+  if (!inplace && (k_out == nullptr || v_out == nullptr)) return RKV_ERR_NULL;
   if ((s = check_ws(pl, ws, ws_bytes)) != RKV_OK) return s;
   if (pl.N <= pl.budget) return RKV_NOT_TRIGGERED;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -194,8 +205,15 @@ static rkv_status compress_impl(const rkv_params* prm, const void* q_obs, const 
     return s;
   if (pl.shared_selection && (s = hip_status(launch_shared_select(pl, w, idx, st))) != RKV_OK) return s;
   if ((s = mark(3)) != RKV_OK) return s;
-  if ((s = hip_status(launch_gather(pl, k, v, idx, k_out, v_out, st))) != RKV_OK) return s;
+  if (inplace) s = hip_status(launch_compact_inplace(pl, const_cast<void*>(k), const_cast<void*>(v), idx, st));
+  else s = hip_status(launch_gather(pl, k, v, idx, k_out, v_out, st));
+  if (s != RKV_OK) return s;
   return mark(4);
+}
+
+rkv_status rkv_compress_inplace(const rkv_params* prm, const void* q_obs, void* k, void* v, int32_t* kept_idx,
+                                float* score, void* ws, size_t ws_bytes, void* stream) {
+  return compress_impl(prm, q_obs, k, v, nullptr, nullptr, kept_idx, score, ws, ws_bytes, stream, nullptr, true);
 }
 
 rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k, const void* v,

@@ -66,6 +66,9 @@ hipError_t launch_shared_select(const Plan& pl, char* ws, int32_t* kept_idx, hip
 hipError_t launch_gather(const Plan& pl, const void* k, const void* v, const int32_t* kept_idx,
                          void* k_out, void* v_out, hipStream_t stream);
 
+// K and V compacted where they lie; kept_idx must be strictly ascending per head.
+hipError_t launch_compact_inplace(const Plan& pl, void* k, void* v, const int32_t* kept_idx, hipStream_t stream);
+
 hipError_t launch_append(const Plan& pl, void* k_cache, void* v_cache, void* q_ring, const void* k_new,
                          const void* v_new, const void* q_new, int pos, int slot, hipStream_t stream);
 

@@ -4,8 +4,9 @@
 N = B_budget + B_buffer rows and the query states of the last alpha decode steps.  Every decode
 step appends one token; when the buffer behind the budget is full the cache is compressed to
 ``budget`` rows (the selected candidates in their original order, then the alpha observation
-tokens) and decoding continues.  Two cache allocations are used alternately so that the
-compaction is a plain gather from one into the other.  All work runs in the HIP library; this
+tokens) and decoding continues.  By default two cache allocations are used alternately so that
+the compaction is a plain gather from one into the other; with ``inplace=True`` there is one
+allocation and the kept rows are moved to its front.  All work runs in the HIP library; this
 class only owns the buffers and the counters.
 """
 from __future__ import annotations
@@ -16,11 +17,13 @@ from . import rkv
 
 
 class DecodeCache:
-    def __init__(self, shape: rkv.Shape, device="cuda"):
+    def __init__(self, shape: rkv.Shape, device="cuda", inplace: bool = False):
         self.shape = shape
+        self.inplace = inplace
         P, H, Hq, N, d = shape.num_problems, shape.kv_heads, shape.q_heads, shape.n_tokens, shape.head_dim
-        self._k = [torch.zeros((P, H, N, d), dtype=torch.bfloat16, device=device) for _ in range(2)]
-        self._v = [torch.zeros((P, H, N, d), dtype=torch.bfloat16, device=device) for _ in range(2)]
+        copies = 1 if inplace else 2
+        self._k = [torch.zeros((P, H, N, d), dtype=torch.bfloat16, device=device) for _ in range(copies)]
+        self._v = [torch.zeros((P, H, N, d), dtype=torch.bfloat16, device=device) for _ in range(copies)]
         self.q_cache = torch.zeros((P, Hq, shape.alpha, d), dtype=torch.bfloat16, device=device)
         self.kept_idx = torch.zeros((P, H, shape.budget), dtype=torch.int32, device=device)
         self._ws = rkv.make_workspace(shape, device)
@@ -55,6 +58,13 @@ class DecodeCache:
         s = self.shape
         if self.length != s.n_tokens:
             raise RuntimeError("compress() runs when the cache holds budget + buffer rows")
+        if self.inplace:
+            st, *_ = rkv.rkv_compress_inplace(s, self.q_cache, self.k, self.v, ws=self._ws, kept_idx=self.kept_idx)
+            if st != rkv.RKV_OK:
+                raise RuntimeError("compression was not triggered")
+            self.length = s.budget
+            self.compressions += 1
+            return
         nxt = 1 - self._cur
         st, *_ = rkv.rkv_compress(s, self.q_cache, self.k, self.v, ws=self._ws,
                                   k_out=self._k[nxt][:, :, :s.budget], v_out=self._v[nxt][:, :, :s.budget],

@@ -70,10 +70,13 @@ def load_library() -> ctypes.CDLL:
     lib.rkv_compact.argtypes = [P, V, V, V, V, V, V]
     lib.rkv_compress.argtypes = [P, V, V, V, V, V, V, V, V, S, V]
     lib.rkv_compress_events.argtypes = [P, V, V, V, V, V, V, V, V, S, V, ctypes.POINTER(ctypes.c_void_p)]
+    lib.rkv_compact_inplace.argtypes = [P, V, V, V, V]
+    lib.rkv_compress_inplace.argtypes = [P, V, V, V, V, V, V, S, V]
     lib.rkv_should_compress.argtypes = [P, ctypes.c_int32]
     lib.rkv_cache_append.argtypes = [P, V, V, V, V, V, V, ctypes.c_int32, ctypes.c_int32, V]
     for name in ("rkv_workspace_size", "rkv_score_importance", "rkv_score_redundancy", "rkv_select_topk",
-                 "rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_should_compress", "rkv_cache_append"):
+                 "rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_should_compress", "rkv_cache_append",
+                 "rkv_compact_inplace", "rkv_compress_inplace"):
         getattr(lib, name).restype = ctypes.c_int
     lib.rkv_status_string.argtypes = [ctypes.c_int]
     lib.rkv_status_string.restype = ctypes.c_char_p
@@ -271,6 +274,48 @@ def rkv_compact(shape: Shape, k: torch.Tensor, v: torch.Tensor, kept_idx: torch.
     if s != RKV_OK:
         raise RkvError(s, "rkv_compact")
     return k_out, v_out
+
+
+def _check_idx(shape: Shape, kept_idx: torch.Tensor) -> None:
+    want = (shape.num_problems, shape.kv_heads, shape.budget)
+    if tuple(kept_idx.shape) != want or kept_idx.dtype != torch.int32 or not kept_idx.is_contiguous():
+        raise ValueError(f"kept_idx must be contiguous int32 {want}")
+
+
+def rkv_compact_inplace(shape: Shape, k: torch.Tensor, v: torch.Tensor, kept_idx: torch.Tensor) -> None:
+    """Move the kept rows (strictly ascending per head) to rows 0 .. budget-1 of k and v themselves."""
+    _need_gpu(k, v, kept_idx)
+    _check_kv(shape, k, "k")
+    _check_kv(shape, v, "v")
+    _check_idx(shape, kept_idx)
+    prm = shape.params(k, v)
+    s = load_library().rkv_compact_inplace(ctypes.byref(prm), _ptr(k), _ptr(v), _ptr(kept_idx), _stream())
+    if s != RKV_OK:
+        raise RkvError(s, "rkv_compact_inplace")
+
+
+def rkv_compress_inplace(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                         ws: Optional[torch.Tensor] = None, kept_idx: Optional[torch.Tensor] = None,
+                         score: Optional[torch.Tensor] = None, want_idx: bool = True, want_score: bool = False):
+    """The whole step with the compaction done inside k and v.  Returns (status, kept_idx, score)."""
+    _need_gpu(q_obs, k, v)
+    _check_q(shape, q_obs)
+    _check_kv(shape, k, "k")
+    _check_kv(shape, v, "v")
+    dev = k.device
+    if kept_idx is None and want_idx:
+        kept_idx = torch.empty((shape.num_problems, shape.kv_heads, shape.budget), dtype=torch.int32, device=dev)
+    if kept_idx is not None:
+        _check_idx(shape, kept_idx)
+    if score is None and want_score:
+        score = torch.empty((shape.num_problems, shape.kv_heads, shape.n_cand), dtype=torch.float32, device=dev)
+    ws, wp, wb = _ws_args(shape, ws, dev)
+    prm = shape.params(k, v)
+    s = load_library().rkv_compress_inplace(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(kept_idx),
+                                            _ptr(score), wp, wb, _stream())
+    if s < 0:
+        raise RkvError(s, "rkv_compress_inplace")
+    return s, kept_idx, score
 
 
 def rkv_compress(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Tensor,

@@ -25,7 +25,7 @@ def declared_symbols(repo_root):
 
 def test_every_declared_symbol_is_exported(lib, repo_root):
     names = declared_symbols(repo_root)
-    assert names == ["rkv_cache_append", "rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_score_importance", "rkv_score_redundancy",
+    assert names == ["rkv_cache_append", "rkv_compact", "rkv_compact_inplace", "rkv_compress", "rkv_compress_events", "rkv_compress_inplace", "rkv_score_importance", "rkv_score_redundancy",
                      "rkv_select_topk", "rkv_should_compress", "rkv_status_string", "rkv_workspace_size"]
     for n in names:
         assert hasattr(lib, n), n
@@ -90,6 +90,10 @@ def test_null_and_workspace_errors_return_before_any_launch(lib):
     # cache does not exceed the budget: nothing to do (Alg. 1 early return)
     p2 = shape(n_tokens=1024, budget=1024).params()
     assert lib.rkv_compress(ctypes.byref(p2), fake, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == rkv.RKV_NOT_TRIGGERED
+    assert lib.rkv_compress_inplace(ctypes.byref(p), fake, None, fake, None, None, fake, 1 << 40, None) == rkv.RKV_ERR_NULL
+    assert lib.rkv_compress_inplace(ctypes.byref(p), fake, fake, fake, None, None, None, 0, None) == rkv.RKV_ERR_WORKSPACE
+    assert lib.rkv_compress_inplace(ctypes.byref(p2), fake, fake, fake, None, None, fake, 1 << 40, None) == rkv.RKV_NOT_TRIGGERED
+    assert lib.rkv_compact_inplace(ctypes.byref(p), fake, fake, None, None) == rkv.RKV_ERR_NULL
     bad = shape().params()
     bad.k_stride_token = 100
     bad.k_stride_head = 8

@@ -517,7 +517,8 @@ def test_largest_supported_cache_sampled_rows():
 
 
 # ------------------------------------------------------------------------------ decode loop
-def test_decode_loop_bookkeeping_and_per_event_parity():
+@pytest.mark.parametrize("inplace", [False, True], ids=["two_buffers", "inplace"])
+def test_decode_loop_bookkeeping_and_per_event_parity(inplace):
     """A synthetic decode run through DecodeCache: appended rows land where they should, the step
     triggers every B_buffer tokens once the cache is full, and every compression event matches the
     oracle run on the cache contents the GPU held at that moment."""
@@ -528,7 +529,7 @@ def test_decode_loop_bookkeeping_and_per_event_parity():
                     pool_w=2, beta=1, sim_threshold=0.5, lam=0.1)
     w = synth.Workload("loop", P, H, H * G, N, budget, alpha=alpha, pool_w=2, beta=1, sim_threshold=0.5, lam=0.1)
     prm = Hp.oracle_params(w)
-    cache = DecodeCache(shp)
+    cache = DecodeCache(shp, inplace=inplace)
     rng = np.random.default_rng(5)
     steps = N + 3 * buffer + 5
     history_k = []
@@ -569,6 +570,86 @@ def test_decode_loop_bookkeeping_and_per_event_parity():
                                before_k[p, h], before_v[p, h], f"event{events}[p{p},h{h}]")
     assert events == cache.compressions == 1 + 3
     assert cache.tokens_seen == steps and cache.length == budget + 5
+
+
+INPLACE_SHAPES = [
+    # P, H, N, budget
+    (2, 2, 384, 256),        # two column slices per row (few heads)
+    (1, 1, 65, 17),          # less than one tile
+    (3, 2, 5000, 4100),      # several tiles, ragged last tile
+    (1, 2, 32768, 1000),     # shifts far larger than a tile
+    (40, 8, 1152, 1024),     # whole rows per workgroup (many heads)
+]
+
+
+def _ascending_lists(rng, P, H, N, budget, pattern):
+    """kept lists [P, H, budget], strictly ascending, of the given eviction pattern."""
+    out = np.empty((P, H, budget), dtype=np.int32)
+    for p in range(P):
+        for h in range(H):
+            if pattern == "front":        # the first N - budget rows are evicted: every row moves by the full shift
+                out[p, h] = np.arange(N - budget, N)
+            elif pattern == "back":       # nothing moves
+                out[p, h] = np.arange(budget)
+            elif pattern == "late":       # one eviction close to the end: almost every row stays
+                cut = max(budget - 3, 0)
+                out[p, h] = np.concatenate([np.arange(cut), np.arange(N - (budget - cut), N)])
+            else:                         # random subset
+                out[p, h] = np.sort(rng.choice(N, size=budget, replace=False))
+    return out
+
+
+@pytest.mark.parametrize("pattern", ["random", "front", "back", "late"])
+@pytest.mark.parametrize("case", INPLACE_SHAPES, ids=lambda c: f"P{c[0]}_H{c[1]}_N{c[2]}_b{c[3]}")
+def test_compact_inplace_moves_rows_without_losing_any(case, pattern):
+    """In-place compaction against the definition (rows kept[r] of the cache as it was, bit for bit)
+    for eviction patterns that stress the overlap of source and destination rows; rows behind the
+    budget keep their old content."""
+    P, H, N, budget = case
+    rng = np.random.default_rng(N + budget)
+    shp = rkv.Shape(num_problems=P, kv_heads=H, q_heads=H, n_tokens=N, budget=budget)
+    kb = rng.integers(0, 1 << 16, size=(P, H, N, 128), dtype=np.uint16)
+    vb = rng.integers(0, 1 << 16, size=(P, H, N, 128), dtype=np.uint16)
+    kept = _ascending_lists(rng, P, H, N, budget, pattern)
+    say(f"rkv_compact_inplace P={P} H={H} N={N} budget={budget} pattern={pattern}")
+    kd, vd = dev_bf16(kb), dev_bf16(vb)
+    rkv.rkv_compact_inplace(shp, kd, vd, torch.from_numpy(kept).cuda())
+    torch.cuda.synchronize()
+    k_after, v_after = host_bits(kd), host_bits(vd)
+    pi, hi = np.arange(P)[:, None, None], np.arange(H)[None, :, None]
+    np.testing.assert_array_equal(k_after[:, :, :budget], kb[pi, hi, kept])
+    np.testing.assert_array_equal(v_after[:, :, :budget], vb[pi, hi, kept])
+    np.testing.assert_array_equal(k_after[:, :, budget:], kb[:, :, budget:])
+    np.testing.assert_array_equal(v_after[:, :, budget:], vb[:, :, budget:])
+
+
+def test_compress_inplace_equals_compress():
+    """The fused step with in-place compaction gives the kept list, scores and rows of rkv_compress,
+    also on strided views of a larger cache allocation."""
+    w = synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=3)
+    q, k, v = synth.make_batch(w)
+    shp = shape_of(w, 3)
+    qd = dev_bf16(q)
+    big_k = torch.zeros((3, w.kv_heads, w.n_tokens + 40, 128), dtype=torch.bfloat16, device="cuda")
+    big_v = torch.zeros_like(big_k)
+    kview, vview = big_k[:, :, 7:7 + w.n_tokens], big_v[:, :, 7:7 + w.n_tokens]
+    kview.copy_(dev_bf16(k))
+    vview.copy_(dev_bf16(v))
+    say("rkv_compress then rkv_compress_inplace on strided views, cfg2 shape P=3")
+    st, ko, vo, idx, score = rkv.rkv_compress(shp, qd, kview, vview, want_idx=True, want_score=True)
+    st2, idx2, score2 = rkv.rkv_compress_inplace(shp, qd, kview, vview, want_idx=True, want_score=True)
+    torch.cuda.synchronize()
+    assert st == st2 == rkv.RKV_OK
+    assert torch.equal(idx, idx2) and torch.equal(score, score2)
+    assert torch.equal(kview[:, :, :w.budget], ko) and torch.equal(vview[:, :, :w.budget], vo)
+    np.testing.assert_array_equal(host_bits(kview[:, :, w.budget:]), k[:, :, w.budget:])
+    assert not big_k[:, :, :7].any() and not big_k[:, :, 7 + w.n_tokens:].any()      # nothing outside the view
+    # not triggered: the cache is left alone
+    calm = rkv.Shape(num_problems=3, kv_heads=w.kv_heads, q_heads=w.q_heads, n_tokens=w.n_tokens, budget=w.n_tokens)
+    before = kview.clone()
+    st3, *_ = rkv.rkv_compress_inplace(calm, qd, kview, vview)
+    torch.cuda.synchronize()
+    assert st3 == rkv.RKV_NOT_TRIGGERED and torch.equal(before, kview)
 
 
 def test_shared_workspace_across_shapes():
