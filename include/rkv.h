@@ -77,6 +77,14 @@ typedef enum {
  */
 #define RKV_FLAG_GQA_SOFTMAX_THEN_MAX 8u
 #define RKV_FLAG_GQA_SOFTMAX_THEN_MEAN 16u
+/*
+ * Direction of the keep-recent rule of Sec. 3.3.  Default (what the text and Alg. 1 both spell out): the
+ * similarity of token i to each of its beta most recent similar tokens j is dropped from token i's own
+ * average.  RKV_FLAG_RECENCY_TRANSPOSED drops it from the recent partner j's average instead, which is
+ * what the stated purpose (keep the most recent of a group of similar tokens) suggests: among exact
+ * copies the newest then has the lowest redundancy.  Needs 8 more workspace bytes per candidate.
+ */
+#define RKV_FLAG_RECENCY_TRANSPOSED 32u
 
 typedef struct {
   int32_t num_problems;      /* P >= 0; an empty batch is valid and enqueues nothing */

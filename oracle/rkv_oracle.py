@@ -21,6 +21,7 @@ Readings taken where the paper is silent or inconsistent (each is a default here
   * "zero the similarities of the beta most recent similar tokens": for token i, among
     the j with S[i][j] > T (strict), the beta largest j have S[i][j] set to 0 before
     token i's own average is taken (Sec. 3.3 and the pseudo-code agree on this);
+    (``recency_transposed`` zeroes the partner's entry S[j][i] instead, see ``forgive_recent``);
   * the average divides by n (zeroed entries included);
   * ties in the top-k are broken towards the larger (more recent) index;
   * kept rows are emitted in ascending original order, followed by the observation rows.
@@ -44,6 +45,7 @@ class Params:
     pool_after_mean: bool = False    # pseudo-code order: mean over the alpha rows, then the pooling
     shared_selection: bool = False   # pseudo-code: scores averaged over the KV heads, one index set
     gqa: str = "max_logits"          # "max_logits" (Eq. 2-3) | "softmax_max" | "softmax_mean" (App. A.2)
+    recency_transposed: bool = False  # the forgiven similarity leaves the recent partner's average instead
 
 
 # ----------------------------------------------------------------------------- decode
@@ -125,12 +127,12 @@ def cosine_similarity(k_cand: np.ndarray, eps: float) -> np.ndarray:
     return S
 
 
-def forgive_recent(S: np.ndarray, T: float, beta: int) -> np.ndarray:
-    """Sec. 3.3 "retention of recent tokens": for each token i take the indices j with
-    S[i, j] > T, and zero S[i, j] for the (up to) beta largest such j."""
-    S = S.copy()
+def recent_similar(S: np.ndarray, T: float, beta: int) -> np.ndarray:
+    """Sec. 3.3: boolean M with M[i, j] true when j is one of the (up to) beta largest indices among
+    the tokens similar to i, i.e. among {j : S[i, j] > T}."""
     n = S.shape[0]
     hit = S > T
+    M = np.zeros_like(hit)
     rev_cols = np.arange(n)[::-1]
     for _ in range(max(0, int(beta))):
         has = hit.any(axis=1)
@@ -138,14 +140,27 @@ def forgive_recent(S: np.ndarray, T: float, beta: int) -> np.ndarray:
             break
         last = rev_cols[np.argmax(hit[:, ::-1], axis=1)]      # largest j with a hit, per row
         rows = np.nonzero(has)[0]
-        S[rows, last[rows]] = 0.0
+        M[rows, last[rows]] = True
         hit[rows, last[rows]] = False
-    return S
+    return M
 
 
-def mean_similarity(k_cand: np.ndarray, T: float, beta: int, eps: float) -> np.ndarray:
+def forgive_recent(S: np.ndarray, T: float, beta: int, transposed: bool = False) -> np.ndarray:
+    """Sec. 3.3 "retention of recent tokens": for each token i and each of its beta most recent
+    similar tokens j, S[i, j] is set to zero (both the text and the pseudo-code say so: token i's own
+    average loses the entry).  ``transposed`` is the other direction, which is what the stated purpose
+    (keep the most recent of a group of similar tokens) suggests: the entry S[j, i] of the recent
+    partner j is zeroed instead, so the most recent copy stops looking redundant and older copies
+    keep their full similarity."""
+    M = recent_similar(S, T, beta)
+    out = S.copy()
+    out[M.T if transposed else M] = 0.0
+    return out
+
+
+def mean_similarity(k_cand: np.ndarray, T: float, beta: int, eps: float, transposed: bool = False) -> np.ndarray:
     """Eq. 6, first part: S-bar[i] = (1/n) sum_j S[i, j] after the zeroing above."""
-    S = forgive_recent(cosine_similarity(k_cand, eps), T, beta)
+    S = forgive_recent(cosine_similarity(k_cand, eps), T, beta, transposed)
     return S.sum(axis=1) / S.shape[0]
 
 
@@ -198,7 +213,7 @@ def compress_head(q_bits: np.ndarray, k_bits: np.ndarray, v_bits: np.ndarray, pr
     q = decode_bf16(q_bits)
     k_cand = decode_bf16(k_bits[:n])
     I = (importance_mean_then_pool if prm.pool_after_mean else importance)(q, k_cand, prm.pool_w, prm.gqa)
-    sbar = mean_similarity(k_cand, float(np.float32(prm.sim_threshold)), prm.beta, prm.eps)
+    sbar = mean_similarity(k_cand, float(np.float32(prm.sim_threshold)), prm.beta, prm.eps, prm.recency_transposed)
     R = softmax_rows(sbar[None, :])[0]
     Z = selection_score(I, R, float(np.float32(prm.lam)))
     keep = select_topk(Z, k_sel)

@@ -8,7 +8,8 @@ namespace rkv {
 
 static constexpr uint32_t kGqaFlags = RKV_FLAG_GQA_SOFTMAX_THEN_MAX | RKV_FLAG_GQA_SOFTMAX_THEN_MEAN;
 static constexpr uint32_t kKnownFlags =
-    RKV_FLAG_SKIP_SATURATED | RKV_FLAG_POOL_AFTER_MEAN | RKV_FLAG_SHARED_SELECTION | kGqaFlags;
+    RKV_FLAG_SKIP_SATURATED | RKV_FLAG_POOL_AFTER_MEAN | RKV_FLAG_SHARED_SELECTION | kGqaFlags |
+    RKV_FLAG_RECENCY_TRANSPOSED;
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -35,6 +36,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->skip_saturated = (q.flags & RKV_FLAG_SKIP_SATURATED) != 0;
   pl->pool_after_mean = (q.flags & RKV_FLAG_POOL_AFTER_MEAN) != 0;
   pl->shared_selection = (q.flags & RKV_FLAG_SHARED_SELECTION) != 0;
+  pl->recency_transposed = (q.flags & RKV_FLAG_RECENCY_TRANSPOSED) != 0;
   pl->gqa_mode = (q.flags & RKV_FLAG_GQA_SOFTMAX_THEN_MAX) ? 1 : ((q.flags & RKV_FLAG_GQA_SOFTMAX_THEN_MEAN) ? 2 : 0);
   pl->qrows = (pl->gqa_mode == 0) ? q.alpha : G * q.alpha;
   pl->heads = q.num_problems * q.kv_heads;
@@ -71,6 +73,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->off_imp = take(heads * np * 4);
   pl->off_red = take(heads * np * 4);
   pl->off_z = take(heads * np * 4);
+  pl->off_credit = take(pl->recency_transposed ? heads * np * 8 : 0);
   pl->off_idx = take(heads * (size_t)pl->budget * 4);
   pl->total = off;
   return RKV_OK;

@@ -24,7 +24,8 @@ constexpr int kMaxPoolFloats = 16384;           // 64 KB of LDS for the pooling 
 struct FinArgs {
   const float* logit;    // [heads][rows][n_pad]
   const float* stats;    // [heads][chunks][rows][2]
-  const float* sbar;     // [heads][n_pad]
+  float* sbar;           // [heads][n_pad]
+  const unsigned long long* credit;   // [heads][n_pad] or nullptr: similarity (units of 2^-40) to take off sbar * n
   const float* imp_in;   // [heads][n] (select-only mode)
   const float* red_in;   // [heads][n]
   float* imp_out;        // [heads][n] or nullptr
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   const int head = blockIdx.x;
   const int n = a.n;
   const float* lg = a.logit + (int64_t)head * a.rows * a.n_pad;
-  const float* sb = a.sbar + (int64_t)head * a.n_pad;
+  float* sb = a.sbar + (int64_t)head * a.n_pad;
 
   // ---- softmax denominators: one wave per query row, lanes over the chunks
   if constexpr ((MODE & kModeImportance) != 0) {
@@ -207,6 +208,13 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   }
   float smax = 0.f, sinv = 0.f;
   if constexpr ((MODE & kModeRedundancy) != 0) {
+    if (a.credit != nullptr) {
+      // transposed recency rule: the similarity pass charged the forgiven entries to the recent
+      // partner; every thread rewrites the elements it reads again below
+      const unsigned long long* cr = a.credit + (int64_t)head * a.n_pad;
+      const float unit = 9.094947017729282e-13f / (float)n;          // 2^-40 / n
+      for (int i = t; i < n; i += kFinThreads) sb[i] -= (float)cr[i] * unit;
+    }
     float m = -INFINITY;
     for (int i = t; i < n; i += kFinThreads) m = fmaxf(m, sb[i]);
     smax = block_max(m, red);
@@ -406,7 +414,8 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   FinArgs a;
   a.logit = reinterpret_cast<const float*>(ws + pl.off_logit);
   a.stats = reinterpret_cast<const float*>(ws + pl.off_stats);
-  a.sbar = reinterpret_cast<const float*>(ws + pl.off_sbar);
+  a.sbar = reinterpret_cast<float*>(ws + pl.off_sbar);
+  a.credit = pl.recency_transposed ? reinterpret_cast<const unsigned long long*>(ws + pl.off_credit) : nullptr;
   a.imp_in = imp_in; a.red_in = red_in;
   a.imp_out = imp_out; a.red_out = red_out; a.sbar_out = sbar_out; a.score_out = score_out;
   a.kept = kept_idx;

@@ -33,6 +33,7 @@ struct GramArgs {
   const float* rnorm;
   const float* upart;
   float* sbar;
+  unsigned long long* credit;   // [heads][n_pad] or nullptr: forgiven similarities charged to the partner
   int H, heads, n, n_pad, chunks, beta, row_blocks, skip_saturated;
   int64_t ksp, ksh, kst;
   float T, eps;
@@ -262,11 +263,22 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
         ++taken;
       }
       const uint32_t take0 = (sel & mine) >> (4 * half);
+      if (a.credit != nullptr) {
+        // the other direction of the rule: the similarity leaves the recent partner's sum, not this
+        // row's.  Integer atomics (units of 2^-40) keep the total independent of the arrival order.
+        const float r_i = rn[row];
+        unsigned long long* cr = a.credit + (int64_t)head * a.n_pad + c0 + 4 * half;
+#pragma unroll
+        for (int i = 15; i >= 0; --i)
+          if ((take0 >> (8 * (i >> 2) + (i & 3))) & 1u)
+            atomicAdd(cr + 8 * (i >> 2) + (i & 3), (unsigned long long)(tv[i] * r_i * 1099511627776.0f));
+      } else {
       float s = 0.f;
 #pragma unroll
       for (int i = 15; i >= 0; --i) s += ((take0 >> (8 * (i >> 2) + (i & 3))) & 1u) ? tv[i] : 0.f;
       s += __shfl_xor(s, 32);                    // both lanes of the row end with the same sum
       sub[rt] += s;
+      }
       cnt[rt] += taken;
       if (cnt[rt] >= a.beta) thr[rt] = INFINITY;
     }
@@ -326,7 +338,11 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
         }
         acc[q2 & 1] = chain(kf[s % KB], res[rt]);
         // the next tile's DMA copies are spread over the steps instead of stalling the wave up front
+#ifdef EXP_PER_STEP
+        constexpr int PER_STEP = EXP_PER_STEP;
+#else
         constexpr int PER_STEP = (LOADS / NW + NS * RT - 1) / (NS * RT);
+#endif
 #pragma unroll
         for (int d = 0; d < PER_STEP; ++d)
           if (q2 * PER_STEP + d < LOADS / NW) issue_rows(ctn, buf ^ 1, q2 * PER_STEP + d, std::false_type{});
@@ -400,6 +416,7 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.rnorm = reinterpret_cast<const float*>(ws + pl.off_rnorm);
   a.upart = reinterpret_cast<const float*>(ws + pl.off_upart);
   a.sbar = reinterpret_cast<float*>(ws + pl.off_sbar);
+  a.credit = pl.recency_transposed ? reinterpret_cast<unsigned long long*>(ws + pl.off_credit) : nullptr;
   a.H = pl.H; a.heads = pl.heads; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks; a.beta = pl.beta;
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   a.T = pl.T; a.eps = pl.eps;

@@ -30,6 +30,7 @@ struct PrepassArgs {
   const uint16_t* q;      // [P, Hq, alpha, d] or nullptr
   const uint16_t* k;
   float* rnorm;
+  unsigned long long* credit;   // zeroed here for the similarity pass, or nullptr
   float* upart;
   float* logit;
   float* stats;
@@ -112,7 +113,10 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
     // hardware sqrt / reciprocal (1 ulp each): r enters every score only through products that are
     // compared at 1e-3 relative, and the threshold test tolerates 1e-5 absolute
     const float r = (grow < a.n) ? __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(ss) + a.eps) : 0.f;
-    if (c16 == 0) a.rnorm[(int64_t)head * a.n_pad + grow] = r;
+    if (c16 == 0) {
+      a.rnorm[(int64_t)head * a.n_pad + grow] = r;
+      if (a.credit) a.credit[(int64_t)head * a.n_pad + grow] = 0ull;
+    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) uacc[e] = fmaf(r, f[e], uacc[e]);
   }
@@ -210,6 +214,7 @@ hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char
   a.k = static_cast<const uint16_t*>(k);
   a.rnorm = reinterpret_cast<float*>(ws + pl.off_rnorm);
   a.upart = reinterpret_cast<float*>(ws + pl.off_upart);
+  a.credit = pl.recency_transposed ? reinterpret_cast<unsigned long long*>(ws + pl.off_credit) : nullptr;
   a.logit = reinterpret_cast<float*>(ws + pl.off_logit);
   a.stats = reinterpret_cast<float*>(ws + pl.off_stats);
   a.H = pl.H; a.G = pl.G; a.alpha = pl.alpha; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks;

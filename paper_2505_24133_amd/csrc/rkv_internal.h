@@ -28,6 +28,7 @@ struct Plan {
   bool skip_saturated;     // RKV_FLAG_SKIP_SATURATED
   bool pool_after_mean;    // RKV_FLAG_POOL_AFTER_MEAN
   bool shared_selection;   // RKV_FLAG_SHARED_SELECTION
+  bool recency_transposed; // RKV_FLAG_RECENCY_TRANSPOSED
   int gqa_mode;            // 0: max of the logits, then softmax (Eq. 2-3); 1: softmax, then max; 2: softmax, then mean
   int qrows;               // logit rows kept per head: alpha (mode 0) or G * alpha
   int64_t ksp, ksh, kst;   // key strides (elements)
@@ -41,6 +42,8 @@ struct Plan {
   size_t off_imp;     // float [heads][n_pad]           importance (fused path)
   size_t off_red;     // float [heads][n_pad]           redundancy (fused path)
   size_t off_z;       // float [heads][n_pad]           per-head scores Z (shared selection)
+  size_t off_credit;  // u64   [heads][n_pad]           forgiven similarity charged to the recent partner, in
+                      //                                units of 2^-40 (RKV_FLAG_RECENCY_TRANSPOSED only)
   size_t off_idx;     // int   [heads][budget]          kept indices when the caller passes none
   size_t total;
 };

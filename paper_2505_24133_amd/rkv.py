@@ -29,6 +29,7 @@ RKV_FLAG_POOL_AFTER_MEAN = 2
 RKV_FLAG_SHARED_SELECTION = 4
 RKV_FLAG_GQA_SOFTMAX_THEN_MAX = 8
 RKV_FLAG_GQA_SOFTMAX_THEN_MEAN = 16
+RKV_FLAG_RECENCY_TRANSPOSED = 32
 
 
 class RkvParams(ctypes.Structure):

@@ -44,6 +44,16 @@ def fragile_rows(k_cand: np.ndarray, T: float, beta: int, eps: float, band: floa
     return (uncertain & (right < beta)).any(axis=1)
 
 
+def fragile_tokens_transposed(k_cand: np.ndarray, T: float, beta: int, eps: float, band: float = SIM_BAND) -> np.ndarray:
+    """With the transposed rule a row's forgiven entries change its partners' scores: the tokens that
+    a threshold-fragile row could name (similarity above T - band) are the ones left unchecked."""
+    rows = fragile_rows(k_cand, T, beta, eps, band)
+    if not rows.any():
+        return rows
+    S = O.cosine_similarity(k_cand, eps)
+    return (S[rows] > T - band).any(axis=0)
+
+
 def exact_topk(z: np.ndarray, k: int) -> np.ndarray:
     """Indices of the k largest entries, equal values resolved towards the larger index, ascending."""
     n = z.shape[0]

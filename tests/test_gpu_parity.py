@@ -41,14 +41,15 @@ def shape_of(w: synth.Workload, P: int) -> rkv.Shape:
 
 
 def check_head(w, ref, z_gpu, kept_gpu, kout, vout, kb, vb, tag, imp=None, red=None, msim=None,
-               z_select=None, frag_select=None):
+               z_select=None, frag_select=None, transposed=False):
     """Compare one head's GPU results with the oracle's dict `ref`.  With the shared selection the
     kept list is the top-k of `z_select` (the head mean of the GPU's scores, formed as the kernel
     forms it) and is compared with the oracle's `shared_score`; `frag_select` marks the candidates
     that are threshold-fragile in any head."""
     n, k = w.n_cand, w.k_sel
     kc = O.decode_bf16(kb[:n])
-    frag = Hp.fragile_rows(kc, float(np.float32(w.sim_threshold)), w.beta, w.eps)
+    frag = (Hp.fragile_tokens_transposed if transposed else Hp.fragile_rows)(
+        kc, float(np.float32(w.sim_threshold)), w.beta, w.eps)
     ok = ~frag
     if imp is not None:
         assert Hp.close(imp, ref["importance"]).all(), f"{tag}: importance"
@@ -118,7 +119,10 @@ def run_fused(w, q, k, v, heads, tag, check_parts=False, flags=0):
     idx_h, score_h = idx.cpu().numpy(), score.cpu().numpy()
     gqa = ("softmax_max" if flags & rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MAX else
            "softmax_mean" if flags & rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MEAN else "max_logits")
-    prm = Hp.oracle_params(w, pool_after_mean=bool(flags & rkv.RKV_FLAG_POOL_AFTER_MEAN), shared_selection=shared, gqa=gqa)
+    transposed = bool(flags & rkv.RKV_FLAG_RECENCY_TRANSPOSED)
+    prm = Hp.oracle_params(w, pool_after_mean=bool(flags & rkv.RKV_FLAG_POOL_AFTER_MEAN), shared_selection=shared, gqa=gqa,
+                           recency_transposed=transposed)
+    frag_of = Hp.fragile_tokens_transposed if transposed else Hp.fragile_rows
     G = w.group
     nfrag = 0
     if shared:
@@ -127,7 +131,7 @@ def run_fused(w, q, k, v, heads, tag, check_parts=False, flags=0):
             refs = O.compress_problem(q[p], k[p], v[p], prm)
             frag_any = np.zeros(n, dtype=bool)
             for h in range(w.kv_heads):
-                frag_any |= Hp.fragile_rows(O.decode_bf16(k[p, h, :n]), float(np.float32(w.sim_threshold)), w.beta, w.eps)
+                frag_any |= frag_of(O.decode_bf16(k[p, h, :n]), float(np.float32(w.sim_threshold)), w.beta, w.eps)
             zbar = head_mean_fp32(score_h[p])
             for h in range(w.kv_heads):
                 assert np.array_equal(idx_h[p, h], idx_h[p, 0]), f"{tag}[p{p}]: heads hold different kept lists"
@@ -135,7 +139,7 @@ def run_fused(w, q, k, v, heads, tag, check_parts=False, flags=0):
                 if parts is not None:
                     extra = dict(imp=parts[0][p, h], red=parts[1][p, h], msim=parts[2][p, h])
                 nfrag += check_head(w, refs[h], score_h[p, h], idx_h[p, h], ko_h[p, h], vo_h[p, h], k[p, h], v[p, h],
-                                    f"{tag}[p{p},h{h}]", z_select=zbar, frag_select=frag_any, **extra)
+                                    f"{tag}[p{p},h{h}]", z_select=zbar, frag_select=frag_any, transposed=transposed, **extra)
         say(f"{tag}: shared selection matches ({nfrag} threshold-fragile rows exempt)")
         return idx, score, ko, vo
     for (p, h) in heads:
@@ -144,7 +148,7 @@ def run_fused(w, q, k, v, heads, tag, check_parts=False, flags=0):
         if parts is not None:
             extra = dict(imp=parts[0][p, h], red=parts[1][p, h], msim=parts[2][p, h])
         nfrag += check_head(w, ref, score_h[p, h], idx_h[p, h], ko_h[p, h], vo_h[p, h], k[p, h], v[p, h],
-                            f"{tag}[p{p},h{h}]", **extra)
+                            f"{tag}[p{p},h{h}]", transposed=transposed, **extra)
     say(f"{tag}: {len(heads)} heads match ({nfrag} threshold-fragile rows exempt)")
     return idx, score, ko, vo
 
@@ -193,19 +197,21 @@ VARIANT_SHAPES = [
     (390, 257, 2, 2, 32, 2, 1, 0.4, 0.2),      # G * alpha = 64 logit rows per head
 ]
 VARIANT_FLAGS = {"mean_then_pool": 2, "shared": 4, "both": 6, "gqa_softmax_max": 8, "gqa_softmax_mean": 16,
-                 "gqa_softmax_max_mean_then_pool_shared": 14, "gqa_softmax_mean_mean_then_pool": 18}
+                 "gqa_softmax_max_mean_then_pool_shared": 14, "gqa_softmax_mean_mean_then_pool": 18,
+                 "recency_transposed": 32, "recency_transposed_shared_skip_saturated": 37}
 
 
 @pytest.mark.parametrize("variant", sorted(VARIANT_FLAGS))
 @pytest.mark.parametrize("case", VARIANT_SHAPES, ids=lambda c: f"N{c[0]}_H{c[2]}_G{c[3]}_a{c[4]}_W{c[5]}")
 def test_pseudo_code_variants(case, variant):
     """The places where the paper's pseudo-code or appendix differ from its equations: mean over the
-    query rows before the pooling, one selection per problem from the head-averaged score, and the
-    query heads of a group merged after their softmax (max or mean)."""
+    query rows before the pooling, one selection per problem from the head-averaged score, the
+    query heads of a group merged after their softmax (max or mean), and the keep-recent rule
+    charged to the recent partner instead of the token itself."""
     N, budget, H, G, alpha, W, beta, T, lam = case
     flags = VARIANT_FLAGS[variant]
     assert (rkv.RKV_FLAG_POOL_AFTER_MEAN, rkv.RKV_FLAG_SHARED_SELECTION, rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MAX,
-            rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MEAN) == (2, 4, 8, 16)
+            rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MEAN, rkv.RKV_FLAG_RECENCY_TRANSPOSED, rkv.RKV_FLAG_SKIP_SATURATED) == (2, 4, 8, 16, 32, 1)
     w = synth.Workload("var", 2, H, H * G, N, budget, alpha=alpha, pool_w=W, beta=beta, sim_threshold=T,
                        lam=lam, seed=500 + N, recipe="rowcopy", redundancy=0.35, copy_noise=0.15)
     q, k, v = synth.make_batch(w)
@@ -222,6 +228,11 @@ def test_pseudo_code_variants_cfg2_full_size():
               flags=rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MAX)
     run_fused(w, q, k, v, [(p, h) for p in (5, 17) for h in range(8)], "cfg2_gqa_softmax_mean",
               flags=rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MEAN)
+    idx1, score1, *_ = run_fused(w, q, k, v, [(p, h) for p in (1, 2, 29) for h in range(8)], "cfg2_recency_transposed",
+                                 flags=rkv.RKV_FLAG_RECENCY_TRANSPOSED)
+    # integer accumulation of the charged similarities: the result does not depend on the arrival order
+    idx2, score2, *_ = run_fused(w, q, k, v, [(11, 4)], "cfg2_recency_transposed_again", flags=rkv.RKV_FLAG_RECENCY_TRANSPOSED)
+    assert torch.equal(idx1, idx2) and torch.equal(score1, score2)
 
 
 def test_cfg2_llama8b_full_size_all_heads():
@@ -334,6 +345,13 @@ def test_exact_duplicates_only_one_copy_survives():
     idx, score, ko, vo = run_fused(w, q, k, v, [(0, 0)], "dups")
     kept = set(idx[0, 0].cpu().numpy().tolist())
     assert [p in kept for p in pos] == [False, False, False, True]
+    # with the rule charged to the recent partner the same outcome needs no tie-break: the newest
+    # copy has strictly the lowest redundancy of the four, the second newest the next lowest
+    idx, score, ko, vo = run_fused(w, q, k, v, [(0, 0)], "dups_transposed", flags=rkv.RKV_FLAG_RECENCY_TRANSPOSED)
+    kept = set(idx[0, 0].cpu().numpy().tolist())
+    assert [p in kept for p in pos] == [False, False, False, True]
+    z = score[0, 0].cpu().numpy()
+    assert z[101] > z[77] > z[40] and abs(z[40] - z[5]) < 1e-7 and abs(z[101] - z[0]) < 1e-6
 
 
 def test_lambda_one_is_attention_only_selection():

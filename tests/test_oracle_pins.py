@@ -276,6 +276,65 @@ def test_golden_recency_rule_three_keys():
                                g["sums_beta2"], atol=1e-15)
 
 
+def test_transposed_recency_rule_golden_brute_force_and_closed_form():
+    """The other direction of the rule: the forgiven entry leaves the recent partner's row."""
+    g = read_golden("recency_rule_three_keys.txt")
+    k3 = g["keys"].reshape(3, 2)
+    S = O.forgive_recent(O.cosine_similarity(k3, 0.0), float(g["T"][0]), 1, transposed=True)
+    np.testing.assert_allclose(S.sum(1), g["sums_transposed"], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(O.mean_similarity(k3, 0.5, 1, 0.0, transposed=True), g["sums_transposed"] / 3,
+                               rtol=1e-12, atol=1e-15)
+    # brute force with explicit loops
+    rng = np.random.default_rng(77)
+    n, d, eps = 28, 5, 1e-8
+    for T, beta in [(0.3, 1), (0.5, 2), (0.0, 4), (0.8, 0)]:
+        k = rng.standard_normal((n, d))
+        for i in rng.integers(1, n, 9):
+            k[i] = k[rng.integers(0, i)] + 0.05 * rng.standard_normal(d)
+        nrm = [math.sqrt(sum(x * x for x in k[i])) + eps for i in range(n)]
+        S = [[0.0 if i == j else sum(k[i, c] * k[j, c] for c in range(d)) / (nrm[i] * nrm[j]) for j in range(n)]
+             for i in range(n)]
+        sums = [sum(S[j]) for j in range(n)]
+        for i in range(n):
+            similar = sorted((j for j in range(n) if S[i][j] > T), reverse=True)
+            for j in similar[:beta]:
+                sums[j] -= S[i][j]                       # token j loses its similarity to i
+        np.testing.assert_allclose(O.mean_similarity(k, T, beta, eps, transposed=True), np.array(sums) / n,
+                                   rtol=1e-11, atol=1e-14)
+    # m exact copies among orthogonal keys, beta = 1: every older copy names the newest, the newest
+    # names the second newest -> newest keeps 0, second newest m - 2, the others m - 1 unit similarities
+    for m in (2, 3, 5):
+        n = 16
+        k = np.zeros((n, n))
+        pos = [1, 4, 6, 9, 13][:m]
+        it = iter(c for c in range(n) if c != 0)
+        for i in range(n):
+            if i in pos:
+                k[i, 0] = 3.0
+            else:
+                k[i, next(it)] = 1.0 + i
+        c = (3.0 / (3.0 + eps)) ** 2
+        ref = np.zeros(n)
+        ref[pos] = (m - 1) * c / n
+        ref[pos[-1]] = 0.0
+        if m >= 2:
+            ref[pos[-2]] = (m - 2) * c / n
+        np.testing.assert_allclose(O.mean_similarity(k, 0.5, 1, eps, transposed=True), ref, rtol=1e-12, atol=1e-15)
+        # strict version of "only one copy survives": lambda = 0, m - 1 evictions remove the older copies
+        bits = synth.f32_to_bf16_bits(k.astype(np.float32))
+        q = np.zeros((1, 1, n), dtype=np.uint16)
+        prm = O.Params(alpha=1, budget=n - (m - 1) + 1, pool_w=0, beta=1, sim_threshold=0.5, lam=0.0, recency_transposed=True)
+        kb = np.concatenate([bits, bits[:1]])            # one observation row behind the n candidates
+        out = O.compress_head(q, kb, kb, prm)
+        if m >= 3:
+            assert sorted(set(range(n)) - set(out["kept"][:-1].tolist())) == pos[:-1]
+    # the totals agree: each forgiven entry is removed from exactly one row in either direction
+    k = rng.standard_normal((n, 6))
+    a = O.forgive_recent(O.cosine_similarity(k, 1e-8), 0.2, 2).sum()
+    b = O.forgive_recent(O.cosine_similarity(k, 1e-8), 0.2, 2, transposed=True).sum()
+    assert abs(a - b) < 1e-12
+
+
 def brute_mean_similarity(k, T, beta, eps):
     n, d = k.shape
     nrm = [math.sqrt(sum(x * x for x in k[i])) + eps for i in range(n)]
