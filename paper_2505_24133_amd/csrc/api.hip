@@ -68,7 +68,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->off_rnorm = take(heads * np * 4);
   pl->off_upart = take(heads * pl->chunks * kHeadDim * 4);
   pl->off_logit = take(heads * pl->qrows * np * 4);
-  pl->off_stats = take(heads * pl->chunks * pl->qrows * 2 * 4);
+  pl->off_stats = take(heads * pl->chunks * 4 * pl->qrows * 2 * 4);
   pl->off_sbar = take(heads * np * 4);
   pl->off_imp = take(heads * np * 4);
   pl->off_red = take(heads * np * 4);

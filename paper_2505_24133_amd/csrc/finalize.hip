@@ -23,7 +23,7 @@ constexpr int kMaxPoolFloats = 16384;           // 64 KB of LDS for the pooling 
 
 struct FinArgs {
   const float* logit;    // [heads][rows][n_pad]
-  const float* stats;    // [heads][chunks][rows][2]
+  const float* stats;    // [heads][stat_groups][rows][2]
   float* sbar;           // [heads][n_pad]
   const unsigned long long* credit;   // [heads][n_pad] or nullptr: similarity (units of 2^-40) to take off sbar * n
   const float* imp_in;   // [heads][n] (select-only mode)
@@ -35,7 +35,7 @@ struct FinArgs {
   float* score_out;      // [heads][n] or nullptr
   float* z_tmp;          // [heads][n_pad] scores for the shared selection, or nullptr
   int32_t* kept;         // [heads][budget]
-  int n, n_pad, chunks, alpha, W, k_sel, budget, pool_floats, pool_rows;
+  int n, n_pad, stat_groups, alpha, W, k_sel, budget, pool_floats, pool_rows;
   int pool_after_mean;
   int rows, G, group_mode;   // rows = logit rows per head: alpha, or G * alpha when group_mode != 0
   float lambda;
@@ -192,12 +192,12 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
     // heads, when that is how they are merged) is folded into the softmax normaliser
     const float parts = (float)a.alpha * (a.group_mode == 2 ? (float)a.G : 1.0f);
     for (int j = t >> 6; j < a.rows; j += kFinWaves) {
-      const float* st = a.stats + ((int64_t)head * a.chunks * a.rows + j) * 2;
+      const float* st = a.stats + ((int64_t)head * a.stat_groups * a.rows + j) * 2;
       float m = -INFINITY;
-      for (int c = lane; c < a.chunks; c += 64) m = fmaxf(m, st[(int64_t)c * a.rows * 2]);
+      for (int c = lane; c < a.stat_groups; c += 64) m = fmaxf(m, st[(int64_t)c * a.rows * 2]);
       m = wave_max(m);
       float den = 0.f;
-      for (int c = lane; c < a.chunks; c += 64)
+      for (int c = lane; c < a.stat_groups; c += 64)
         den += st[(int64_t)c * a.rows * 2 + 1] * expf(st[(int64_t)c * a.rows * 2] - m);
       den = wave_sum(den);
       if (lane == 0) {
@@ -419,7 +419,7 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   a.imp_in = imp_in; a.red_in = red_in;
   a.imp_out = imp_out; a.red_out = red_out; a.sbar_out = sbar_out; a.score_out = score_out;
   a.kept = kept_idx;
-  a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks; a.alpha = pl.alpha; a.W = pl.W;
+  a.n = pl.n; a.n_pad = pl.n_pad; a.stat_groups = pl.chunks * (prepass_register_path(pl) ? 4 : 1); a.alpha = pl.alpha; a.W = pl.W;
   a.k_sel = pl.k_sel; a.budget = pl.budget;
   a.lambda = pl.lambda;
   a.imp_tmp = reinterpret_cast<float*>(ws + pl.off_imp);

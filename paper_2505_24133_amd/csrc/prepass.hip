@@ -40,7 +40,11 @@ struct PrepassArgs {
   float eps, scale;
 };
 
-template <bool HAS_Q, int MT>
+// AH = alpha / 2 selects the register path for the usual window sizes (alpha = 8, 16 or 32 with
+// G * alpha <= 32): with those, the query rows that one accumulator register holds for g = 0 .. G-1
+// sit AH registers apart in the same lane, so the max over the group and the wave's softmax
+// statistics need neither LDS nor a workgroup barrier.  AH = 0 is the general path.
+template <bool HAS_Q, int MT, int AH>
 __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a) {
   // The logit tile reuses the key tile's LDS once every wave has read its key fragments
   // (MT * 32 rows x 136 floats <= 128 rows x 272 bytes), which lets four workgroups share a CU.
@@ -159,6 +163,36 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf, acc[mt], 0, 0, 0);
       }
     }
+    if constexpr (AH > 0) {
+      static_assert(MT == 1, "the register path covers G * alpha <= 32");
+      // accumulator element i: key = lane % 32 of this wave's 32 keys, query row g * alpha + j with
+      // g = i / AH and j = 8 * ((i % AH) / 4) + 4 * (lane / 32) + i % 4
+      const int key = j0 + wave * 32 + lrow;
+      const bool valid = key < a.n;
+      float* lgt = a.logit + (int64_t)head * a.alpha * a.n_pad + key;
+      float* st = a.stats + ((int64_t)head * a.chunks * 4 + chunk * 4 + wave) * a.alpha * 2;
+#pragma unroll
+      for (int i = 0; i < AH; ++i) {
+        float m = acc[0][i];
+#pragma unroll
+        for (int g = 1; g < 16 / AH; ++g)
+          if (g < a.G) m = fmaxf(m, acc[0][i + g * AH]);
+        m *= a.scale;
+        const int j = 8 * (i >> 2) + 4 * khalf + (i & 3);
+        if (valid) lgt[(int64_t)j * a.n_pad] = m;
+        // (max, sum exp) over the wave's 32 keys: the butterfly stays inside each half of the wave
+        float mx = valid ? m : -INFINITY;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        float e = valid ? expf(m - mx) : 0.f;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) e += __shfl_xor(e, o);
+        if (lrow == 0) {
+          st[j * 2] = mx;
+          st[j * 2 + 1] = e;
+        }
+      }
+    } else {
     __syncthreads();      // all key fragments are in registers: the tile can be overwritten
     // accumulator layout: column (key) = lane % 32, row (query) = 8*(i/4) + 4*(lane/32) + i%4
 #pragma unroll
@@ -197,6 +231,7 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
         st[1] = s;
       }
     }
+    }  // general path
   }
   __syncthreads();          // the tiles are rewritten by the next item
   if (has_next) {
@@ -206,7 +241,27 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
   }  // items
 }
 
+// As many workgroups as stay resident at once (queried once per kernel variant), each walking over
+// its share of the items.
+template <bool HAS_Q, int MT, int AH>
+void launch_variant(const PrepassArgs& a, hipStream_t stream) {
+  static const int res = [] {
+    int per_cu = 0, dev = 0, cus = 0;
+    const void* fn = reinterpret_cast<const void*>(&prepass_kernel<HAS_Q, MT, AH>);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kPrepassThreads, 0) != hipSuccess || per_cu < 1) per_cu = 2;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    return per_cu * cus;
+  }();
+  const dim3 grid((unsigned)std::min(a.items, res)), block(kPrepassThreads);
+  hipLaunchKernelGGL((prepass_kernel<HAS_Q, MT, AH>), grid, block, 0, stream, a);
+}
+
 }  // namespace
+
+int prepass_register_path(const Plan& pl) {
+  const bool usual = pl.alpha == 8 || pl.alpha == 16 || pl.alpha == 32;
+  return (usual && pl.gqa_mode == 0 && pl.G * pl.alpha <= 32) ? pl.alpha / 2 : 0;
+}
 
 hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char* ws, hipStream_t stream) {
   PrepassArgs a;
@@ -223,25 +278,13 @@ hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char
   a.eps = pl.eps;
   a.scale = 1.0f / sqrtf((float)kHeadDim);
   a.items = pl.heads * pl.chunks;
-  // as many workgroups as stay resident at once (queried once per kernel variant)
-  auto resident = [](const void* fn) {
-    int per_cu = 0, dev = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kPrepassThreads, 0) != hipSuccess || per_cu < 1) per_cu = 2;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
-    return per_cu * cus;
-  };
-  static const int res_noq = resident(reinterpret_cast<const void*>(&prepass_kernel<false, 1>));
-  static const int res_q1 = resident(reinterpret_cast<const void*>(&prepass_kernel<true, 1>));
-  static const int res_q2 = resident(reinterpret_cast<const void*>(&prepass_kernel<true, 2>));
-  const int res = (q_obs == nullptr) ? res_noq : (pl.G * pl.alpha <= 32 ? res_q1 : res_q2);
-  const dim3 grid((unsigned)std::min(a.items, res)), block(kPrepassThreads);
-  if (q_obs == nullptr) {
-    hipLaunchKernelGGL((prepass_kernel<false, 1>), grid, block, 0, stream, a);
-  } else if (pl.G * pl.alpha <= 32) {
-    hipLaunchKernelGGL((prepass_kernel<true, 1>), grid, block, 0, stream, a);
-  } else {
-    hipLaunchKernelGGL((prepass_kernel<true, 2>), grid, block, 0, stream, a);
-  }
+  const int fast = prepass_register_path(pl);      // alpha / 2, or 0
+  if (q_obs == nullptr) launch_variant<false, 1, 0>(a, stream);
+  else if (fast == 4) launch_variant<true, 1, 4>(a, stream);
+  else if (fast == 8) launch_variant<true, 1, 8>(a, stream);
+  else if (fast == 16) launch_variant<true, 1, 16>(a, stream);
+  else if (pl.G * pl.alpha <= 32) launch_variant<true, 1, 0>(a, stream);
+  else launch_variant<true, 2, 0>(a, stream);
   return hipGetLastError();
 }
 

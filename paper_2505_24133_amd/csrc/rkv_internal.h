@@ -37,7 +37,8 @@ struct Plan {
   size_t off_rnorm;   // float [heads][n_pad]           1 / (|K_i| + eps), 0 for i >= n
   size_t off_upart;   // float [heads][chunks][128]     per-chunk sums of r_i K_i
   size_t off_logit;   // float [heads][qrows][n_pad]    scaled logits (group max in mode 0)
-  size_t off_stats;   // float [heads][chunks][qrows][2] per-chunk (max, sum exp)
+  size_t off_stats;   // float [heads][groups][qrows][2] (max, sum exp) per chunk (groups = chunks), or per
+                      //                                 32 keys (groups = 4 * chunks) on the pre-pass's register path
   size_t off_sbar;    // float [heads][n_pad]           mean similarity
   size_t off_imp;     // float [heads][n_pad]           importance (fused path)
   size_t off_red;     // float [heads][n_pad]           redundancy (fused path)
@@ -51,6 +52,9 @@ struct Plan {
 rkv_status make_plan(const rkv_params* prm, Plan* plan);
 
 // Kernel launchers (each enqueues on `stream` and returns hipGetLastError()).
+// alpha / 2 when the pre-pass merges the group's heads in registers and writes its softmax statistics
+// per 32 keys, 0 when it goes through LDS and writes them per chunk of 128 keys.
+int prepass_register_path(const Plan& pl);
 hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char* ws, hipStream_t stream);
 hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stream);
 

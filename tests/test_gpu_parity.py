@@ -174,6 +174,10 @@ ADVERSARIAL = [
     (390, 257, 1, 2, 32, 0, 64, 0.4, 0.2),    # G * alpha = 64 rows, beta larger than any hit count
     (700, 650, 1, 4, 8, 400, 1, 0.5, 0.3),    # pooling window wider than the cache
     (2100, 1900, 1, 4, 8, 4, 2, 0.5, 0.1),    # more than one staging block in the pooling stage
+    (500, 300, 2, 2, 16, 3, 1, 0.5, 0.1),     # alpha = 16, G = 2: the pre-pass's register path, 8 values per lane
+    (333, 200, 1, 1, 32, 2, 1, 0.5, 0.2),     # alpha = 32, MHA: register path, 16 values per lane
+    (420, 300, 2, 1, 8, 4, 1, 0.5, 0.1),      # alpha = 8, MHA: register path with a single head per group
+    (150, 100, 1, 2, 8, 4, 1, 0.5, 0.1),      # n = 142: the last chunk's third and fourth 32-key groups are empty
 ]
 
 
