@@ -66,6 +66,48 @@ def cpu_baseline(w, q, k, v, seconds: float):
                       f"extrapolated linearly to one step (all heads)"}
 
 
+def other_modes(torch, rkv, synth, w, shp, qd, kd, vd, ws, ko, vo, idx, reps=50):
+    """The same workload launched in other ways, for context next to the headline figure (ms per step):
+    one call per layer back to back on one stream (eager, and replayed from a HIP graph), a high
+    threshold at which only true near-duplicates count as similar, and attention-only eviction
+    (lambda = 1, no similarity pass)."""
+    import dataclasses
+
+    def timed(fn):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    res = {}
+    one = dataclasses.replace(shp, num_problems=1)
+    layers = range(w.num_problems)
+
+    def per_layer():
+        for l in layers:
+            rkv.rkv_compress(one, qd[l:l + 1], kd[l:l + 1], vd[l:l + 1], ws=ws, k_out=ko[l:l + 1], v_out=vo[l:l + 1],
+                             kept_idx=idx[l:l + 1])
+    res["per_layer_calls_ms"] = timed(per_layer)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        per_layer()                                  # every kernel has run once before the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        per_layer()
+    res["per_layer_calls_hip_graph_ms"] = timed(graph.replay)
+    for name, change in (("sim_threshold_0.95_ms", {"sim_threshold": 0.95}), ("attention_only_lambda_1_ms", {"lam": 1.0})):
+        alt = dataclasses.replace(shp, **change)
+        res[name] = timed(lambda: rkv.rkv_compress(alt, qd, kd, vd, ws=ws, k_out=ko, v_out=vo, kept_idx=idx))
+    return {k_: float(v_) for k_, v_ in res.items()}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -208,6 +250,8 @@ def main() -> int:
         "stages": {s: {kk: float(vv) for kk, vv in st.items()} for s, st in stages.items()},
         "roofline": roofline,
     }
+    if not args.skip_saturated and args.sim_threshold is None and args.beta is None and args.lam is None:
+        out["other_modes"] = other_modes(torch, rkv, synth, w, shp, qd, kd, vd, ws, ko, vo, idx)
     if args.skip_saturated:
         out["config"]["flags"] = "RKV_FLAG_SKIP_SATURATED"
         out["roofline"] = None          # executed matrix work is data dependent in this mode

@@ -674,6 +674,48 @@ def test_compress_inplace_equals_compress():
     assert st3 == rkv.RKV_NOT_TRIGGERED and torch.equal(before, kview)
 
 
+def test_hip_graph_replays_match_eager():
+    """rkv_compress captured into a HIP graph (the library enqueues kernels only: no allocation, no
+    memset, no host synchronisation) and replayed on fresh inputs, with eager work between the
+    replays; every replay must equal the eager call on the same inputs."""
+    w = synth.scaled(synth.CONFIGS["cfg1_tiny"], num_problems=3)
+    shp = shape_of(w, 3)
+    batches = [synth.make_batch(synth.scaled(w, seed=900 + i)) for i in range(3)]
+    qs, ks, vs = (torch.empty_like(dev_bf16(x)) for x in batches[0])
+    ws = rkv.make_workspace(shp)
+    ko = torch.empty((3, w.kv_heads, w.budget, 128), dtype=torch.bfloat16, device="cuda")
+    vo = torch.empty_like(ko)
+    idx = torch.empty((3, w.kv_heads, w.budget), dtype=torch.int32, device="cuda")
+    score = torch.empty((3, w.kv_heads, w.n_cand), dtype=torch.float32, device="cuda")
+
+    def call():
+        st = rkv.rkv_compress(shp, qs, ks, vs, ws=ws, k_out=ko, v_out=vo, kept_idx=idx, score=score)[0]
+        assert st == rkv.RKV_OK
+
+    say("graph capture of rkv_compress, cfg1 shape P=3")
+    qs.copy_(dev_bf16(batches[0][0])), ks.copy_(dev_bf16(batches[0][1])), vs.copy_(dev_bf16(batches[0][2]))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()                                       # first call outside the capture (one-time kernel set-up)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for r, (q, k, v) in enumerate(batches + batches[:1]):
+        say(f"replay {r}")
+        qs.copy_(dev_bf16(q)), ks.copy_(dev_bf16(k)), vs.copy_(dev_bf16(v))
+        ko.zero_(), vo.zero_(), idx.zero_(), score.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (ko.clone(), vo.clone(), idx.clone(), score.clone())
+        st, ko2, vo2, idx2, score2 = rkv.rkv_compress(shp, dev_bf16(q), dev_bf16(k), dev_bf16(v), want_idx=True, want_score=True)
+        torch.cuda.synchronize()
+        assert torch.equal(got[2], idx2) and torch.equal(got[3], score2), f"replay {r}: indices or scores differ"
+        assert torch.equal(got[0], ko2) and torch.equal(got[1], vo2), f"replay {r}: compacted rows differ"
+
+
 def test_shared_workspace_across_shapes():
     """One oversized workspace reused by calls of different shapes: nothing read is left over from
     an earlier call."""
