@@ -2,6 +2,8 @@
 // Nothing here touches device memory from the host or synchronises the stream.
 #include <math.h>
 
+#include <algorithm>
+
 #include "rkv_internal.h"
 
 namespace rkv {
@@ -62,6 +64,23 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
     if (!strides(q.o_stride_problem, q.o_stride_head, q.o_stride_token, &pl->osp, &pl->osh, &pl->ost)) return RKV_ERR_SHAPE;
   }
 
+  // ---- how the similarity pass is cut into workgroups (two are resident per compute unit): when the
+  // row blocks of all heads would leave most of the machine idle, the column scan of every row block
+  // is split over several workgroups
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+      (void)hipGetLastError();          // no device (host-only use of the size query): assume the MI355X
+      cus = 256;
+    }
+    const int64_t slots = 2 * cus;
+    const int64_t blocks = (int64_t)pl->heads * ((pl->n + kGramRows - 1) / kGramRows);
+    const int nct = (pl->n + kGramTile - 1) / kGramTile;
+    pl->gram_parts = 1;
+    if (pl->beta == 1 && !pl->recency_transposed && blocks > 0 && blocks <= slots / 2)
+      pl->gram_parts = (int)std::max<int64_t>(1, std::min<int64_t>(std::min(nct, 16), slots / blocks));
+  }
+
   size_t off = 0;
   const size_t heads = (size_t)pl->heads, np = (size_t)pl->n_pad;
   auto take = [&](size_t bytes) { const size_t o = off; off = align_up(off + bytes); return o; };
@@ -74,6 +93,9 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->off_red = take(heads * np * 4);
   pl->off_z = take(heads * np * 4);
   pl->off_credit = take(pl->recency_transposed ? heads * np * 8 : 0);
+  const size_t parts = (size_t)pl->gram_parts;
+  pl->off_pcnt = take(parts > 1 ? heads * parts * np * 4 : 0);
+  pl->off_ppre = take(parts > 1 ? heads * parts * np * 4 : 0);
   pl->off_idx = take(heads * (size_t)pl->budget * 4);
   pl->total = off;
   return RKV_OK;

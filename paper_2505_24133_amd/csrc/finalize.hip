@@ -36,6 +36,12 @@ struct FinArgs {
   float* z_tmp;          // [heads][n_pad] scores for the shared selection, or nullptr
   int32_t* kept;         // [heads][budget]
   int n, n_pad, stat_groups, alpha, W, k_sel, budget, pool_floats, pool_rows;
+  // similarity rows whose column scan was split over several workgroups: per-part hit counts and
+  // running sums, merged here (most recent part first) before the softmax
+  const float* rnorm;    // [heads][n_pad]
+  const int* part_cnt;   // [heads][parts][n_pad]
+  const float* part_pre; // [heads][parts][n_pad]
+  int parts;
   int pool_after_mean;
   int rows, G, group_mode;   // rows = logit rows per head: alpha, or G * alpha when group_mode != 0
   float lambda;
@@ -208,6 +214,22 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   }
   float smax = 0.f, sinv = 0.f;
   if constexpr ((MODE & kModeRedundancy) != 0) {
+    if (a.parts > 1) {
+      // beta = 1 (the only case that is split): the most recent column part that found a hit supplies
+      // the forgiven similarity
+      const float inv_n = 1.0f / (float)n;
+      for (int i = t; i < n; i += kFinThreads) {
+        float forgiven = 0.f;
+        for (int p = a.parts - 1; p >= 0; --p) {
+          const int64_t at = ((int64_t)head * a.parts + p) * a.n_pad + i;
+          if (a.part_cnt[at] > 0) {
+            forgiven = a.part_pre[at];
+            break;
+          }
+        }
+        sb[i] -= a.rnorm[(int64_t)head * a.n_pad + i] * forgiven * inv_n;
+      }
+    }
     if (a.credit != nullptr) {
       // transposed recency rule: the similarity pass charged the forgiven entries to the recent
       // partner; every thread rewrites the elements it reads again below
@@ -426,6 +448,10 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   a.z_tmp = reinterpret_cast<float*>(ws + pl.off_z);
   a.pool_after_mean = pl.pool_after_mean ? 1 : 0;
   a.rows = pl.qrows; a.G = pl.G; a.group_mode = pl.gqa_mode;
+  a.rnorm = reinterpret_cast<const float*>(ws + pl.off_rnorm);
+  a.part_cnt = reinterpret_cast<const int*>(ws + pl.off_pcnt);
+  a.part_pre = reinterpret_cast<const float*>(ws + pl.off_ppre);
+  a.parts = pl.gram_parts;
   a.pool_rows = pl.alpha + a.pool_after_mean;
   // dynamic LDS: the select keys (n_pad words) and the pooling stage share one region
   size_t words = (mode & kModeSelect) ? (size_t)pl.n_pad : 0;

@@ -18,6 +18,7 @@
 // the 16-byte fragment reads hit without bank conflicts.  Per 32x32 tile the common-case
 // epilogue is one multiply per element folded into a running max, issued in the shadow of the
 // next tile's MFMA chain; K_i . u comes from three extra pseudo-keys (u split into bf16 pieces).
+#include <algorithm>
 #include <type_traits>
 
 #include "rkv_internal.h"
@@ -34,7 +35,10 @@ struct GramArgs {
   const float* upart;
   float* sbar;
   unsigned long long* credit;   // [heads][n_pad] or nullptr: forgiven similarities charged to the partner
-  int H, heads, n, n_pad, chunks, beta, row_blocks, skip_saturated;
+  int* part_cnt;                // [heads][parts][n_pad] hits per row found by one column part
+  float* part_pre;              // [heads][parts][n_pad] their sum
+  int H, heads, n, n_pad, chunks, beta, skip_saturated;
+  int row_blocks, parts;        // workgroups per head = row_blocks * parts
   int64_t ksp, ksh, kst;
   float T, eps;
 };
@@ -63,7 +67,13 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t l
                : "memory");
 }
 
-template <int NW, int RT, int TC, int WPS>
+// Kernel variants (the common one carries none of the others' code):
+//   kPlain       one workgroup scans all columns of its rows and writes the mean similarity
+//   kSplit       the scan is shared by several workgroups, each reports what it found (beta = 1)
+//   kTransposed  forgiven similarities are charged to the recent partner's counter
+enum GramVariant : int { kPlain = 0, kSplit = 1, kTransposed = 2 };
+
+template <int NW, int RT, int TC, int WPS, int VARIANT>
 __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   // WPS = waves per SIMD the register budget is cut for: 2 keeps two sets of key fragments and r_j
   // (prefetch one subtile ahead), 3 keeps one set and relies on the other waves to hide LDS latency.
@@ -82,11 +92,17 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
 
   // Workgroups are dealt round-robin to the 8 XCDs; give every XCD whole heads so that a head's
   // keys are fetched into one L2 only.
+  // Workgroups are dealt round-robin to the 8 XCDs; give every XCD whole heads so that a head's
+  // keys are fetched into one L2 only.  A head's workgroups (row block x column part) are adjacent.
   const int b = blockIdx.x;
   const int xcd = b & 7;
   const int q = b >> 3;
-  const int head = (q / a.row_blocks) * 8 + xcd;
-  const int rb = q % a.row_blocks;
+  const int parts = (VARIANT == kSplit) ? a.parts : 1;
+  const int per_head = a.row_blocks * parts;
+  const int head = (q / per_head) * 8 + xcd;
+  const int rem = q % per_head;
+  const int rb = rem / parts;
+  const int part = rem - rb * parts;
   if (head >= a.heads) return;
 
   const int t = threadIdx.x;
@@ -138,8 +154,14 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     for (int jj = 0; jj < LOADS / NW; ++jj) issue_rows(ct, buf, jj, std::true_type{});
     issue_rj(ct, buf);
   };
-  const int nct = (a.beta > 0) ? (n + TC - 1) / TC : 0;
-  if (nct > 0) issue_tile(nct - 1, 0);
+  // this workgroup's share of the column tiles: [ct_lo, ct_hi), scanned from ct_hi - 1 downwards
+  const int nct_all = (a.beta > 0) ? (n + TC - 1) / TC : 0;
+  const int ct_lo = (int)((int64_t)part * nct_all / parts);
+  const int ct_hi = (int)((int64_t)(part + 1) * nct_all / parts);
+  const int nct = ct_hi - ct_lo;
+  const bool split = parts > 1;
+  const bool closing = part == parts - 1;           // the part that also writes the closed-form row sums
+  if (nct > 0) issue_tile(ct_hi - 1, 0);
 
   // ---- prologue: u -> three bf16 pseudo-keys, the wave's rows -> registers
   {
@@ -174,6 +196,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     thr[rt] = (row < n && a.beta > 0) ? a.T / rn[row] : INFINITY;
     sub[rt] = 0.f;
     cnt[rt] = 0;
+    rowdot[rt] = 0.f;
   }
   __syncthreads();
   if (t < kHeadDim) {
@@ -218,7 +241,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     return acc;
   };
   // K_i . u = sum of the three pseudo-key columns (accumulator elements 0..2 of lanes with half == 0)
-  if (active) {
+  if (active && closing) {
     bf16x8 pf[8];
     read_k(pf, gram_lds, 0);
 #pragma unroll
@@ -263,7 +286,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
         ++taken;
       }
       const uint32_t take0 = (sel & mine) >> (4 * half);
-      if (a.credit != nullptr) {
+      if (VARIANT == kTransposed) {
         // the other direction of the rule: the similarity leaves the recent partner's sum, not this
         // row's.  Integer atomics (units of 2^-40) keep the total independent of the arrival order.
         const float r_i = rn[row];
@@ -295,11 +318,11 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
 
   // ---- stream the tiles, most recent first
   for (int it = 0; it < nct; ++it) {
-    const int ct = nct - 1 - it;
+    const int ct = ct_hi - 1 - it;
     const int buf = it & 1;
-    // The next tile is copied while this one is used.  The last iteration copies tile 0 once more
+    // The next tile is copied while this one is used.  The last iteration copies its own tile once more
     // (harmless, never read) so that the copy needs no branch inside the MFMA/VALU pipeline below.
-    const int ctn = max(ct - 1, 0);
+    const int ctn = max(ct - 1, ct_lo);
     issue_rj(ctn, buf ^ 1);
     const unsigned char* tile = gram_lds + OFF_TILE + buf * TILE_SPAN;
     const float* rjs = reinterpret_cast<const float*>(gram_lds + OFF_RJ + buf * TC * 4);
@@ -383,28 +406,37 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
       if (row < n) {
         const float r = rn[row];
         const float self = 1.0f - a.eps * r;               // r_i |K_i| = 1 - eps r_i
-        const float total = r * rowdot[rt] - self * self - r * sub[rt];
-        a.sbar[(int64_t)head * a.n_pad + row] = total / (float)n;
+        if (!split) {
+          const float total = r * rowdot[rt] - self * self - r * sub[rt];
+          a.sbar[(int64_t)head * a.n_pad + row] = total / (float)n;
+        } else {
+          // finalize subtracts the forgiven similarity once every part has reported its hit (beta = 1:
+          // the most recent part that found one supplies it)
+          a.part_cnt[((int64_t)head * parts + part) * a.n_pad + row] = cnt[rt];
+          a.part_pre[((int64_t)head * parts + part) * a.n_pad + row] = sub[rt];
+          if (closing) a.sbar[(int64_t)head * a.n_pad + row] = (r * rowdot[rt] - self * self) / (float)n;
+        }
       }
     }
   }
 }
 
-template <int NW, int RT, int TC, int WPS>
+template <int NW, int RT, int TC, int WPS, int VARIANT>
 hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   constexpr int BM = NW * RT * 32;
   constexpr size_t lds = kPseudoBytes + 2 * (size_t)TC * kRowBytes + 2 * (size_t)TC * 4;
   static bool configured = false;
   if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS, VARIANT>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  a.row_blocks = (pl.n + BM - 1) / BM;
+  static_assert(BM == kGramRows && TC == kGramTile, "the plan's split of the similarity pass assumes this shape");
   const int head_groups = (pl.heads + 7) / 8;
-  const dim3 grid((unsigned)((int64_t)head_groups * a.row_blocks * 8));
-  hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS>), grid, dim3(NW * 64), lds, stream, a);
+  a.row_blocks = (pl.n + BM - 1) / BM;
+  const dim3 grid((unsigned)((int64_t)head_groups * 8 * a.row_blocks * a.parts));
+  hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS, VARIANT>), grid, dim3(NW * 64), lds, stream, a);
   return hipGetLastError();
 }
 
@@ -420,12 +452,16 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.H = pl.H; a.heads = pl.heads; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks; a.beta = pl.beta;
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   a.T = pl.T; a.eps = pl.eps;
-  a.row_blocks = 0;
+  a.row_blocks = 0; a.parts = pl.gram_parts;
+  a.part_cnt = reinterpret_cast<int*>(ws + pl.off_pcnt);
+  a.part_pre = reinterpret_cast<float*>(ws + pl.off_ppre);
   a.skip_saturated = pl.skip_saturated ? 1 : 0;
 #ifdef EXP_SHAPE
-  return launch_shape<EXP_SHAPE>(a, pl, stream);
+  return launch_shape<EXP_SHAPE, kPlain>(a, pl, stream);
 #else
-  return launch_shape<4, 2, 128, 2>(a, pl, stream);
+  if (a.credit != nullptr) return launch_shape<4, 2, 128, 2, kTransposed>(a, pl, stream);
+  if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit>(a, pl, stream);
+  return launch_shape<4, 2, 128, 2, kPlain>(a, pl, stream);
 #endif
 }
 

@@ -12,6 +12,8 @@ namespace rkv {
 constexpr int kHeadDim = 128;        // d
 constexpr int kChunk = 128;          // keys per workgroup in the key pre-pass
 constexpr int kMaxQRows = 64;        // G * alpha rows of observation queries per KV head
+constexpr int kGramRows = 256;       // candidate rows per workgroup of the similarity pass
+constexpr int kGramTile = 128;       // keys per streamed column tile of the similarity pass
 constexpr int kRowBytes = kHeadDim * 2;
 constexpr int kLdsRowBytes = kRowBytes + 16;   // padded LDS row: 16-byte fragments of 8 consecutive rows hit distinct banks
 
@@ -29,6 +31,10 @@ struct Plan {
   bool pool_after_mean;    // RKV_FLAG_POOL_AFTER_MEAN
   bool shared_selection;   // RKV_FLAG_SHARED_SELECTION
   bool recency_transposed; // RKV_FLAG_RECENCY_TRANSPOSED
+  // Similarity pass: the column scan of every row block is split over `gram_parts` workgroups when
+  // there are too few row blocks to fill the machine (beta = 1 only: each part reports the first hit of
+  // its own column range and finalize keeps the most recent one).
+  int gram_parts;
   int gqa_mode;            // 0: max of the logits, then softmax (Eq. 2-3); 1: softmax, then max; 2: softmax, then mean
   int qrows;               // logit rows kept per head: alpha (mode 0) or G * alpha
   int64_t ksp, ksh, kst;   // key strides (elements)
@@ -45,6 +51,8 @@ struct Plan {
   size_t off_z;       // float [heads][n_pad]           per-head scores Z (shared selection)
   size_t off_credit;  // u64   [heads][n_pad]           forgiven similarity charged to the recent partner, in
                       //                                units of 2^-40 (RKV_FLAG_RECENCY_TRANSPOSED only)
+  size_t off_pcnt;    // int   [heads][gram_parts][n_pad]    hits found per row and column part (gram_parts > 1)
+  size_t off_ppre;    // float [heads][gram_parts][n_pad]    sum of those hits
   size_t off_idx;     // int   [heads][budget]          kept indices when the caller passes none
   size_t total;
 };

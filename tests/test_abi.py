@@ -66,7 +66,7 @@ def test_workspace_size_and_validation(lib):
     assert ws_status(lib, shape(flags=8 | 16))[0] == rkv.RKV_ERR_PARAM             # two ways of merging the group at once
     # merging after the softmax keeps G * alpha logit rows per head: a larger workspace
     assert ws_status(lib, shape(flags=8))[1] > ws_status(lib, shape())[1]
-    assert ws_status(lib, shape(flags=32))[1] > ws_status(lib, shape())[1]         # 8 more bytes per candidate
+    assert ws_status(lib, shape(flags=32, beta=2))[1] > ws_status(lib, shape(beta=2))[1]     # 8 more bytes per candidate
     # pooling stage holds alpha rows, one more when the mean is taken before the pooling
     assert ws_status(lib, shape(alpha=63, q_heads=8, pool_w=130))[0] == rkv.RKV_OK            # 63 * 260 <= 16384
     assert ws_status(lib, shape(alpha=63, q_heads=8, pool_w=130, flags=2))[0] == rkv.RKV_ERR_UNSUPPORTED
