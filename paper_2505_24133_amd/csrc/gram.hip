@@ -163,37 +163,44 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   const bool closing = part == parts - 1;           // the part that also writes the closed-form row sums
   if (nct > 0) issue_tile(ct_hi - 1, 0);
 
-  // ---- prologue: u -> three bf16 pseudo-keys, the wave's rows -> registers
+  // ---- prologue: u -> three bf16 pseudo-keys, the wave's rows -> registers.  Every global load of
+  // the prologue is issued before anything waits for one of them (one memory latency, not four):
+  // rows past n read row n - 1 (their results are never written and their threshold is +inf).
+  bf16x8 res[RT][8];
+  float thr[RT], sub[RT], rowdot[RT], rni[RT];
+  int cnt[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int rowc = min(i0 + rt * 32 + lrow, n - 1);
+    rni[rt] = rn[rowc];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const uint4 x = *reinterpret_cast<const uint4*>(kbase + (int64_t)rowc * a.kst + kk * 16 + half * 8);
+      __builtin_memcpy(&res[rt][kk], &x, 16);
+    }
+  }
   {
-    // u = sum of the pre-pass's per-chunk partials, in a fixed order; all threads load in parallel
+    // u = sum of the pre-pass's per-chunk partials, in a fixed order; all threads load in parallel,
+    // eight chunks per thread in flight
     constexpr int GROUPS = NT / kHeadDim;
     float* ured = reinterpret_cast<float*>(gram_lds + OFF_TILE + TILE_SPAN);   // tile 1 is not in use yet
     const int e = t & (kHeadDim - 1), grp = t >> 7;
     const float* up = a.upart + (int64_t)head * a.chunks * kHeadDim + e;
-    float u0 = 0.f, u1 = 0.f, u2 = 0.f, u3 = 0.f;
-    int c = grp;
-    for (; c + 3 * GROUPS < a.chunks; c += 4 * GROUPS) {
-      u0 += up[(int64_t)c * kHeadDim];
-      u1 += up[(int64_t)(c + GROUPS) * kHeadDim];
-      u2 += up[(int64_t)(c + 2 * GROUPS) * kHeadDim];
-      u3 += up[(int64_t)(c + 3 * GROUPS) * kHeadDim];
+    float usum = 0.f;
+    for (int c0 = grp; c0 < a.chunks; c0 += 8 * GROUPS) {
+      float x[8];
+#pragma unroll
+      for (int q2 = 0; q2 < 8; ++q2) x[q2] = up[(int64_t)min(c0 + q2 * GROUPS, a.chunks - 1) * kHeadDim];
+#pragma unroll
+      for (int q2 = 0; q2 < 8; ++q2) x[q2] = (c0 + q2 * GROUPS < a.chunks) ? x[q2] : 0.f;
+      usum += ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
     }
-    for (; c < a.chunks; c += GROUPS) u0 += up[(int64_t)c * kHeadDim];
-    ured[t] = (u0 + u1) + (u2 + u3);
+    ured[t] = usum;
   }
-  bf16x8 res[RT][8];
-  float thr[RT], sub[RT], rowdot[RT];
-  int cnt[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     const int row = i0 + rt * 32 + lrow;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      uint4 x = make_uint4(0, 0, 0, 0);
-      if (row < n) x = *reinterpret_cast<const uint4*>(kbase + (int64_t)row * a.kst + kk * 16 + half * 8);
-      __builtin_memcpy(&res[rt][kk], &x, 16);
-    }
-    thr[rt] = (row < n && a.beta > 0) ? a.T / rn[row] : INFINITY;
+    thr[rt] = (row < n && a.beta > 0) ? a.T / rni[rt] : INFINITY;
     sub[rt] = 0.f;
     cnt[rt] = 0;
     rowdot[rt] = 0.f;
@@ -460,7 +467,7 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   return launch_shape<EXP_SHAPE, kPlain>(a, pl, stream);
 #else
   if (a.credit != nullptr) return launch_shape<4, 2, 128, 2, kTransposed>(a, pl, stream);
-  if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit>(a, pl, stream);
+  if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit>(a, pl, stream);       // split only with beta = 1
   return launch_shape<4, 2, 128, 2, kPlain>(a, pl, stream);
 #endif
 }
