@@ -19,7 +19,7 @@ namespace {
 
 constexpr int kFinThreads = 1024;
 constexpr int kFinWaves = kFinThreads / 64;
-constexpr int kMaxPoolFloats = 16384;           // 64 KB of LDS for the pooling stage
+constexpr int kMaxPoolFloats = 16384 + 4 * (kMaxQRows + 1);   // about 65 KB of LDS for the pooling stage
 
 struct FinArgs {
   const float* logit;    // [heads][rows][n_pad]
@@ -106,17 +106,22 @@ __device__ __forceinline__ uint32_t order_key(float z) {
 // Exact top-k of the n keys held in LDS (equal keys: larger index first).  The k_sel selected indices
 // are written in ascending order, followed by n .. n + alpha - 1, to `copies` output lists that lie
 // `copy_stride` ints apart.  All threads of the workgroup call this; `keys` must be complete (the
-// caller synchronises before the call).
+// caller synchronises before the call).  `hist` holds 4 x 256 counters, `sel` 4 x 3 words.
+//
+// Four 8-bit radix passes find the key of the k-th largest score: each pass counts the digits of the
+// keys that match the digits fixed so far (one histogram per pass, all zeroed up front) and the first
+// wave alone locates the bin that holds the k-th largest, so a pass costs two workgroup barriers.
 __device__ void select_and_emit(const uint32_t* keys, int n, int k_sel, int alpha, int32_t* out, int copies,
                                 int64_t copy_stride, uint32_t* hist, uint32_t* scan_buf, uint32_t* sel) {
   const int t = threadIdx.x;
   const int lane = t & 63;
-  // ---- radix select: key of the k-th largest score
+  for (int i = t; i < 4 * 256; i += kFinThreads) hist[i] = 0;
+  __syncthreads();
   uint32_t prefix = 0, known = 0, krem = (uint32_t)k_sel, n_equal = 0;
 #pragma unroll 1
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    if (t < 256) hist[t] = 0;
-    __syncthreads();
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    uint32_t* h = hist + pass * 256;
     for (int i0 = 0; i0 < n; i0 += kFinThreads) {
       const int i = i0 + t;
       const uint32_t key = (i < n) ? keys[i] : 0u;
@@ -128,47 +133,59 @@ __device__ void select_and_emit(const uint32_t* keys, int n, int k_sel, int alph
         const int first = __ffsll((long long)am) - 1;
         const uint32_t d0 = __shfl(digit, first);
         const unsigned long long same = __ballot(live && digit == d0);
-        if (lane == first) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+        if (lane == first) atomicAdd(&h[d0], (uint32_t)__popcll(same));
         live = live && (digit != d0);
-        if (live) atomicAdd(&hist[digit], 1u);
+        if (live) atomicAdd(&h[digit], 1u);
       }
     }
     __syncthreads();
-    // the bin holding the krem-th largest: bins above it hold fewer than krem keys
-    uint32_t total = 0;
-    const uint32_t mine = (t < 256) ? hist[255 - t] : 0u;      // thread t <-> bin 255 - t
-    const uint32_t above = block_exclusive_scan(mine, scan_buf, &total);
-    if (t < 256 && above < krem && above + mine >= krem) {
-      sel[0] = 255u - (uint32_t)t;
-      sel[1] = above;
-      sel[2] = mine;
+    if (t < 64) {
+      // lane l looks at bins 255 - 4l .. 252 - 4l, i.e. the bins in descending order; the bin holding
+      // the krem-th largest key is the one whose bins above it hold fewer than krem keys
+      const uint32_t b0 = h[255 - 4 * lane], b1 = h[254 - 4 * lane], b2 = h[253 - 4 * lane], b3 = h[252 - 4 * lane];
+      const uint32_t mine = (b0 + b1) + (b2 + b3);
+      uint32_t inc = mine;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t y = __shfl_up(inc, o);
+        if (lane >= o) inc += y;
+      }
+      const uint32_t a0 = inc - mine, a1 = a0 + b0, a2 = a1 + b1, a3 = a2 + b2;
+      uint32_t* s3 = sel + pass * 3;
+      if (a0 < krem && a1 >= krem) { s3[0] = 255u - 4u * lane; s3[1] = a0; s3[2] = b0; }
+      if (a1 < krem && a2 >= krem) { s3[0] = 254u - 4u * lane; s3[1] = a1; s3[2] = b1; }
+      if (a2 < krem && a3 >= krem) { s3[0] = 253u - 4u * lane; s3[1] = a2; s3[2] = b2; }
+      if (a3 < krem && a3 + b3 >= krem) { s3[0] = 252u - 4u * lane; s3[1] = a3; s3[2] = b3; }
     }
     __syncthreads();
-    prefix |= sel[0] << shift;
+    prefix |= sel[pass * 3] << shift;
     known |= 255u << shift;
-    krem -= sel[1];
-    n_equal = sel[2];
-    __syncthreads();
+    krem -= sel[pass * 3 + 1];
+    n_equal = sel[pass * 3 + 2];
   }
-  // keys > prefix are all kept; of the n_equal keys == prefix the krem with the largest indices
+  // keys > prefix are all kept; of the n_equal keys == prefix the krem with the largest indices.
+  // Each thread owns a run of consecutive candidates, so one workgroup scan orders the output.
   const uint32_t skip_eq = n_equal - krem;
-  uint32_t run_gt = 0, run_eq = 0;
-  for (int i0 = 0; i0 < n; i0 += kFinThreads) {
-    const int i = i0 + t;
-    const uint32_t key = (i < n) ? keys[i] : 0u;
-    const uint32_t gt = (i < n && key > prefix) ? 1u : 0u;
-    const uint32_t eq = (i < n && key == prefix) ? 1u : 0u;
-    uint32_t total;
-    const uint32_t ex = block_exclusive_scan(gt | (eq << 16), scan_buf, &total);
-    const uint32_t gt_before = run_gt + (ex & 0xffffu);
-    const uint32_t eq_before = run_eq + (ex >> 16);
-    const bool keep = gt || (eq && eq_before >= skip_eq);
-    if (keep) {
+  const int per = (n + kFinThreads - 1) / kFinThreads;
+  const int lo = min(t * per, n), hi = min(lo + per, n);
+  uint32_t gt = 0, eq = 0;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t key = keys[i];
+    gt += key > prefix ? 1u : 0u;
+    eq += key == prefix ? 1u : 0u;
+  }
+  uint32_t total;
+  const uint32_t ex = block_exclusive_scan(gt | (eq << 16), scan_buf, &total);
+  uint32_t gt_before = ex & 0xffffu, eq_before = ex >> 16;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t key = keys[i];
+    const bool is_gt = key > prefix, is_eq = key == prefix;
+    if (is_gt || (is_eq && eq_before >= skip_eq)) {
       const uint32_t pos = gt_before + (eq_before > skip_eq ? eq_before - skip_eq : 0u);
       for (int c = 0; c < copies; ++c) out[c * copy_stride + pos] = i;
     }
-    run_gt += total & 0xffffu;
-    run_eq += total >> 16;
+    gt_before += is_gt ? 1u : 0u;
+    eq_before += is_eq ? 1u : 0u;
   }
   for (int r = t; r < alpha; r += kFinThreads)
     for (int c = 0; c < copies; ++c) out[c * copy_stride + k_sel + r] = n + r;
@@ -178,12 +195,12 @@ constexpr int kModeZ = kModeSelect | kModeScore;     // modes that form the join
 
 template <int MODE>
 __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
-  extern __shared__ uint32_t keys[];            // n_pad order-preserving keys (select mode) / pooling stage
+  extern __shared__ __attribute__((aligned(16))) uint32_t keys[];   // n_pad order-preserving keys (select mode) / pooling stage
   __shared__ float red[kFinWaves];
   __shared__ uint32_t scan_buf[kFinWaves];
   __shared__ float gmax[kMaxQRows], ginv[kMaxQRows];
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t sel[3];
+  __shared__ uint32_t hist[4 * 256];
+  __shared__ uint32_t sel[4 * 3];
 
   const int t = threadIdx.x;
   const int lane = t & 63;
@@ -254,10 +271,15 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
     float* pool = reinterpret_cast<float*>(keys);            // the key buffer is not in use yet
     const int win = (a.W > 0) ? 2 * a.W : 1;
     const int halo = win - 1;
-    const int block_cols = min(a.pool_floats / a.pool_rows, 2 * kFinThreads) - halo;  // >= 1 (checked on the host)
+    // columns per staging block: a multiple of four, leaving room for the window behind the last one
+    const int block_cols = (min(a.pool_floats / a.pool_rows, 2 * kFinThreads) - win) & ~3;   // >= 4 (checked on the host)
+    // W even: four neighbouring candidates share all but three entries of their windows, so one thread
+    // serves four candidates from 16-byte LDS reads
+    const bool strips = win >= 4 && (win & 3) == 0;
     for (int cb = 0; cb < n; cb += block_cols) {
       const int cols = min(block_cols, n - cb);
       const int width = cols + halo;
+      const int stride = ((cols + 3) & ~3) + win;              // floats per staged row, a multiple of four if `strips`
       const int first = cb - a.W;                              // column held at pool[j][0]
       if (a.group_mode != 0) {
         // App. A.2 variants: the attention scores of every query head first (softmax per head), then
@@ -303,25 +325,25 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
         __syncthreads();
         continue;
       }
-      // four query rows x two column slots: eight independent loads per thread are in flight
+      // eight query rows x two column slots: sixteen independent loads per thread are in flight
       // before the first LDS store (width <= 2 * kFinThreads by the choice of block_cols)
-      for (int j0 = 0; j0 < a.alpha; j0 += 4) {
-        float v[4][2];
+      for (int j0 = 0; j0 < a.alpha; j0 += 8) {
+        float v[8][2];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
           for (int sl = 0; sl < 2; ++sl) {
             const int c = t + sl * kFinThreads;
             const int col = first + c;
             v[u][sl] = (j0 + u < a.alpha && c < width && col >= 0 && col < n)
-                           ? lg[(int64_t)(j0 + u) * a.n_pad + col] : -INFINITY;
+                           ? lg[(int64_t)(j0 + u) * a.n_pad + col] : -INFINITY;      // -inf also fills width .. stride - 1
           }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
           for (int sl = 0; sl < 2; ++sl) {
             const int c = t + sl * kFinThreads;
-            if (j0 + u < a.alpha && c < width) pool[(j0 + u) * width + c] = v[u][sl];
+            if (j0 + u < a.alpha && c < stride) pool[(j0 + u) * stride + c] = v[u][sl];
           }
       }
       __syncthreads();
@@ -329,10 +351,10 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
         // Alg. 1 order: the mean over the query rows of the attention weights first (one extra LDS
         // row; columns outside [0, n) hold exp(-inf) = 0, which never wins a max over weights >= 0
         // because every window holds its own column), then the sliding max of that row
-        float* avg = pool + a.alpha * width;
+        float* avg = pool + a.alpha * stride;
         for (int c = t; c < width; c += kFinThreads) {
           float s = 0.f;
-          for (int j = 0; j < a.alpha; ++j) s += __expf(pool[j * width + c] - gmax[j]) * ginv[j];
+          for (int j = 0; j < a.alpha; ++j) s += __expf(pool[j * stride + c] - gmax[j]) * ginv[j];
           avg[c] = s;
         }
         __syncthreads();
@@ -340,6 +362,38 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
           float m = avg[li];
           for (int c = 1; c < win; ++c) m = fmaxf(m, avg[li + c]);
           imp_dst[cb + li] = m;
+        }
+        __syncthreads();
+        continue;
+      }
+      if (strips) {
+        const int chunks = win >> 2;
+        for (int g = t; 4 * g < cols; g += kFinThreads) {
+          float imp[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+          for (int j = 0; j < a.alpha; ++j) {
+            // candidates 4g .. 4g+3 of this block: windows [4g + k, 4g + k + win - 1] in staged numbering
+            const float4* rowp = reinterpret_cast<const float4*>(pool + j * stride + 4 * g);
+            const float4 head4 = rowp[0];
+            float inner = head4.w;                               // entries 3 .. win-1 belong to all four windows
+            for (int q2 = 1; q2 < chunks; ++q2) {
+              const float4 x = rowp[q2];
+              inner = fmaxf(inner, fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w)));
+            }
+            const float4 tail4 = rowp[chunks];
+            const float o0 = fmaxf(fmaxf(inner, head4.x), fmaxf(head4.y, head4.z));
+            const float o1 = fmaxf(fmaxf(inner, head4.y), fmaxf(head4.z, tail4.x));
+            const float o2 = fmaxf(fmaxf(inner, head4.z), fmaxf(tail4.x, tail4.y));
+            const float o3 = fmaxf(fmaxf(inner, tail4.x), fmaxf(tail4.y, tail4.z));
+            const float gm = gmax[j], gi = ginv[j];
+            imp[0] += __expf(o0 - gm) * gi;
+            imp[1] += __expf(o1 - gm) * gi;
+            imp[2] += __expf(o2 - gm) * gi;
+            imp[3] += __expf(o3 - gm) * gi;
+          }
+#pragma unroll
+          for (int k2 = 0; k2 < 4; ++k2)
+            if (4 * g + k2 < cols) imp_dst[cb + 4 * g + k2] = imp[k2];
         }
         __syncthreads();
         continue;
@@ -354,7 +408,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
           for (int c = 0; c < win; ++c) {
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-              if (j0 + u < a.alpha) m[u] = fmaxf(m[u], pool[(j0 + u) * width + li + c]);   // window [i - W, i + W - 1]
+              if (j0 + u < a.alpha) m[u] = fmaxf(m[u], pool[(j0 + u) * stride + li + c]);   // window [i - W, i + W - 1]
           }
 #pragma unroll
           for (int u = 0; u < 8; ++u)
@@ -401,8 +455,8 @@ __global__ __launch_bounds__(kFinThreads) void shared_select_kernel(const float*
                                                                     int n_pad, int k_sel, int alpha, int budget) {
   extern __shared__ uint32_t keys[];
   __shared__ uint32_t scan_buf[kFinWaves];
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t sel[3];
+  __shared__ uint32_t hist[4 * 256];
+  __shared__ uint32_t sel[4 * 3];
   const int p = blockIdx.x;
   const float inv_h = 1.0f / (float)H;
   for (int i = threadIdx.x; i < n; i += kFinThreads) {
@@ -458,8 +512,8 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   a.pool_floats = 0;
   if (mode & kModeImportance) {
     const int win = pl.W > 0 ? 2 * pl.W : 1;
-    const size_t want = (size_t)a.pool_rows * (size_t)(std::min(pl.n, 2048) + win - 1);
-    const size_t least = (size_t)a.pool_rows * (size_t)win;       // one column per block at the very least
+    const size_t want = (size_t)a.pool_rows * (size_t)(std::min(pl.n + 3, 2048 - win) + win);
+    const size_t least = (size_t)a.pool_rows * (size_t)(win + 4); // four columns per block at the very least
     size_t pool = std::min(std::max(want, least), (size_t)kMaxPoolFloats);
     if (pool < least) return hipErrorInvalidValue;                // rejected earlier by make_plan
     a.pool_floats = (int)pool;
