@@ -26,6 +26,28 @@ __device__ __forceinline__ float dpp_add(float v) {
   return v + __int_as_float(x);
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v) {
+  const int x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return fmaxf(v, __int_as_float(x));
+}
+// Reductions over the 32 lanes of each half of the wave (every lane of the half ends with the result):
+// four DPP steps inside the rows of 16 lanes, one cross-lane exchange between the two rows.
+__device__ __forceinline__ float half_wave_max(float v) {
+  v = dpp_max<0xB1>(v);     // quad_perm [1,0,3,2]
+  v = dpp_max<0x4E>(v);     // quad_perm [2,3,0,1]
+  v = dpp_max<0x141>(v);    // row_half_mirror
+  v = dpp_max<0x140>(v);    // row_mirror
+  return fmaxf(v, __shfl_xor(v, 16));
+}
+__device__ __forceinline__ float half_wave_sum(float v) {
+  v = dpp_add<0xB1>(v);
+  v = dpp_add<0x4E>(v);
+  v = dpp_add<0x141>(v);
+  v = dpp_add<0x140>(v);
+  return v + __shfl_xor(v, 16);
+}
+
 struct PrepassArgs {
   const uint16_t* q;      // [P, Hq, alpha, d] or nullptr
   const uint16_t* k;
@@ -59,8 +81,9 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
   const int c16 = t & 15;
   const int rbase = t >> 4;
 
-  // Persistent workgroups: each walks over (head, chunk) items and fetches the next item's keys
-  // into registers while it works on the current one, so HBM requests are always in flight.
+  // Persistent workgroups: each walks over (head, chunk) items.  Four workgroups share a compute unit
+  // (128 VGPRs, 37 KB of LDS each), so while one waits for its chunk the others compute; holding the
+  // next chunk in registers as well cost a workgroup per compute unit and was slower.
   auto fetch = [&](int item, uint4 (&dst)[8]) {
     const int hd = item / a.chunks;
     const int ck = item - hd * a.chunks;
@@ -73,8 +96,7 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
       if (grow < a.n) dst[m] = *reinterpret_cast<const uint4*>(kb + (int64_t)grow * a.kst + c16 * 8);
     }
   };
-  uint4 regs[8], next[8];
-  if ((int)blockIdx.x < a.items) fetch(blockIdx.x, regs);
+  uint4 regs[8];
 
   for (int item = blockIdx.x; item < a.items; item += gridDim.x) {
   const int head = item / a.chunks;
@@ -82,8 +104,23 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
   const int p = head / a.H;
   const int h = head - p * a.H;
   const int j0 = chunk * kChunk;
-  const bool has_next = item + (int)gridDim.x < a.items;
-  if (has_next) fetch(item + gridDim.x, next);
+  fetch(item, regs);
+  // the query fragments of this head are requested now and used after the norms: their latency hides
+  // behind the first stage (rows past G * alpha repeat the last one; their results are not read)
+  bf16x8 qf[MT][8];
+  if constexpr (HAS_Q) {
+    const int GA = a.G * a.alpha;
+    const uint16_t* qbase = a.q + ((int64_t)p * a.H * a.G + (int64_t)h * a.G) * a.alpha * kHeadDim;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int qrow = min(mt * 32 + (lane & 31), GA - 1);
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const uint4 qv = *reinterpret_cast<const uint4*>(qbase + qrow * kHeadDim + kk * 16 + (lane >> 5) * 8);
+        __builtin_memcpy(&qf[mt][kk], &qv, 16);
+      }
+    }
+  }
 
   // ---- stage the chunk in LDS, norms and the chunk's share of u
   float uacc[8];
@@ -141,8 +178,6 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
 
   if constexpr (HAS_Q) {
     // ---- logits: A = the G*alpha query rows of this KV head, B = 32 keys per wave
-    const int GA = a.G * a.alpha;
-    const uint16_t* qbase = a.q + ((int64_t)p * a.H * a.G + (int64_t)h * a.G) * a.alpha * kHeadDim;
     f32x16 acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -154,14 +189,7 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
     for (int kk = 0; kk < 8; ++kk) {
       const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + (wave * 32 + lrow) * kLdsRowBytes + kk * 32 + khalf * 16);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int qrow = mt * 32 + lrow;
-        uint4 qv = make_uint4(0, 0, 0, 0);
-        if (qrow < GA) qv = *reinterpret_cast<const uint4*>(qbase + qrow * kHeadDim + kk * 16 + khalf * 8);
-        bf16x8 qf;
-        __builtin_memcpy(&qf, &qv, 16);
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf, acc[mt], 0, 0, 0);
-      }
+      for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], kf, acc[mt], 0, 0, 0);
     }
     if constexpr (AH > 0) {
       static_assert(MT == 1, "the register path covers G * alpha <= 32");
@@ -171,25 +199,28 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
       const bool valid = key < a.n;
       float* lgt = a.logit + (int64_t)head * a.alpha * a.n_pad + key;
       float* st = a.stats + ((int64_t)head * a.chunks * 4 + chunk * 4 + wave) * a.alpha * 2;
+      // stage by stage over the lane's AH query rows, so that the cross-lane steps of different rows
+      // are in flight together
+      float m[AH], mx[AH], e[AH];
 #pragma unroll
       for (int i = 0; i < AH; ++i) {
-        float m = acc[0][i];
+        m[i] = acc[0][i];
 #pragma unroll
         for (int g = 1; g < 16 / AH; ++g)
-          if (g < a.G) m = fmaxf(m, acc[0][i + g * AH]);
-        m *= a.scale;
-        const int j = 8 * (i >> 2) + 4 * khalf + (i & 3);
-        if (valid) lgt[(int64_t)j * a.n_pad] = m;
-        // (max, sum exp) over the wave's 32 keys: the butterfly stays inside each half of the wave
-        float mx = valid ? m : -INFINITY;
+          if (g < a.G) m[i] = fmaxf(m[i], acc[0][i + g * AH]);
+        m[i] *= a.scale;
+        if (valid) lgt[(int64_t)(8 * (i >> 2) + 4 * khalf + (i & 3)) * a.n_pad] = m[i];
+      }
+      // (max, sum exp) over the wave's 32 keys of each row
 #pragma unroll
-        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-        float e = valid ? expf(m - mx) : 0.f;
+      for (int i = 0; i < AH; ++i) mx[i] = half_wave_max(valid ? m[i] : -INFINITY);
 #pragma unroll
-        for (int o = 16; o > 0; o >>= 1) e += __shfl_xor(e, o);
-        if (lrow == 0) {
-          st[j * 2] = mx;
-          st[j * 2 + 1] = e;
+      for (int i = 0; i < AH; ++i) e[i] = half_wave_sum(valid ? expf(m[i] - mx[i]) : 0.f);
+      if (lrow == 0) {
+#pragma unroll
+        for (int i = 0; i < AH; ++i) {
+          const int j = 8 * (i >> 2) + 4 * khalf + (i & 3);
+          *reinterpret_cast<float2*>(st + j * 2) = make_float2(mx[i], e[i]);
         }
       }
     } else {
@@ -234,10 +265,6 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
     }  // general path
   }
   __syncthreads();          // the tiles are rewritten by the next item
-  if (has_next) {
-#pragma unroll
-    for (int m = 0; m < 8; ++m) regs[m] = next[m];
-  }
   }  // items
 }
 
