@@ -32,20 +32,20 @@ __device__ __forceinline__ float dpp_max(float v) {
   return fmaxf(v, __int_as_float(x));
 }
 // Reductions over the 32 lanes of each half of the wave (every lane of the half ends with the result):
-// four DPP steps inside the rows of 16 lanes, one cross-lane exchange between the two rows.
+// four DPP steps inside the rows of 16 lanes, one row swap between the two rows.
 __device__ __forceinline__ float half_wave_max(float v) {
   v = dpp_max<0xB1>(v);     // quad_perm [1,0,3,2]
   v = dpp_max<0x4E>(v);     // quad_perm [2,3,0,1]
   v = dpp_max<0x141>(v);    // row_half_mirror
   v = dpp_max<0x140>(v);    // row_mirror
-  return fmaxf(v, __shfl_xor(v, 16));
+  return pair_max16(v);
 }
 __device__ __forceinline__ float half_wave_sum(float v) {
   v = dpp_add<0xB1>(v);
   v = dpp_add<0x4E>(v);
   v = dpp_add<0x141>(v);
   v = dpp_add<0x140>(v);
-  return v + __shfl_xor(v, 16);
+  return pair_sum16(v);
 }
 
 struct PrepassArgs {
@@ -89,11 +89,11 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
     const int ck = item - hd * a.chunks;
     const int pp = hd / a.H;
     const uint16_t* kb = a.k + pp * a.ksp + (hd - pp * a.H) * a.ksh;
+    // rows past n repeat row n - 1 (their r is forced to 0 below and their logits are masked)
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
-      const int grow = ck * kChunk + m * 16 + rbase;
-      dst[m] = make_uint4(0, 0, 0, 0);
-      if (grow < a.n) dst[m] = *reinterpret_cast<const uint4*>(kb + (int64_t)grow * a.kst + c16 * 8);
+      const int grow = min(ck * kChunk + m * 16 + rbase, a.n - 1);
+      dst[m] = *reinterpret_cast<const uint4*>(kb + (int64_t)grow * a.kst + c16 * 8);
     }
   };
   uint4 regs[8];
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
   }
 
   // ---- stage the chunk in LDS, norms and the chunk's share of u
-  float uacc[8];
+  float uacc[8], r8[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) uacc[e] = 0.f;
 #pragma unroll
@@ -154,18 +154,23 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
     // hardware sqrt / reciprocal (1 ulp each): r enters every score only through products that are
     // compared at 1e-3 relative, and the threshold test tolerates 1e-5 absolute
     const float r = (grow < a.n) ? __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(ss) + a.eps) : 0.f;
-    if (c16 == 0) {
-      a.rnorm[(int64_t)head * a.n_pad + grow] = r;
-      if (a.credit) a.credit[(int64_t)head * a.n_pad + grow] = 0ull;
-    }
+    r8[m] = r;
 #pragma unroll
     for (int e = 0; e < 8; ++e) uacc[e] = fmaf(r, f[e], uacc[e]);
   }
+  if (c16 == 0) {
+    // one lane per row writes r (0 in the padding up to n_pad) and clears the partner counter
+    float* rn = a.rnorm + (int64_t)head * a.n_pad + j0 + rbase;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    uacc[e] += __shfl_xor(uacc[e], 16);
-    uacc[e] += __shfl_xor(uacc[e], 32);
+    for (int m = 0; m < 8; ++m) rn[m * 16] = r8[m];
+    if (a.credit) {
+      unsigned long long* cr = a.credit + (int64_t)head * a.n_pad + j0 + rbase;
+#pragma unroll
+      for (int m = 0; m < 8; ++m) cr[m * 16] = 0ull;
+    }
   }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) uacc[e] = pair_sum32(pair_sum16(uacc[e]));
   if (lane < 16) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) ured[wave][lane * 8 + e] = uacc[e];
