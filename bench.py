@@ -27,7 +27,7 @@ HBM_PEAK = 8.0e12            # B/s
 # HBM bytes per launch of the similarity (Gram) kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this same command, scaled by a plain 256 MiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 KiB);
 # the runs are summarised in profiles/rkv_compress_cfg2_counters.md.
-GRAM_TRAFFIC_BYTES = {"cfg2_llama8b_b1024": int((4.315e4 * 2.0 + 1144) * 1024)}
+GRAM_TRAFFIC_BYTES = {"cfg2_llama8b_b1024": int((4.451e4 * 2.0 + 1144) * 1024)}
 
 
 def hip_runtime(torch):
@@ -122,6 +122,8 @@ def main() -> int:
     ap.add_argument("--skip-saturated", action="store_true",
                     help="set RKV_FLAG_SKIP_SATURATED (exact, data-dependent shortcut of the similarity pass); "
                          "the roofline entry is then not meaningful and is omitted")
+    ap.add_argument("--no-other-modes", action="store_true",
+                    help="skip the extra launch modes reported for context (per-layer calls, T = 0.95, attention-only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -250,7 +252,7 @@ def main() -> int:
         "stages": {s: {kk: float(vv) for kk, vv in st.items()} for s, st in stages.items()},
         "roofline": roofline,
     }
-    if not args.skip_saturated and args.sim_threshold is None and args.beta is None and args.lam is None:
+    if not (args.skip_saturated or args.no_other_modes) and args.sim_threshold is None and args.beta is None and args.lam is None:
         out["other_modes"] = other_modes(torch, rkv, synth, w, shp, qd, kd, vd, ws, ko, vo, idx)
     if args.skip_saturated:
         out["config"]["flags"] = "RKV_FLAG_SKIP_SATURATED"
