@@ -62,9 +62,9 @@ struct PrepassArgs {
   float eps, scale;
 };
 
-// AH = alpha / 2 selects the register path for the usual window sizes (alpha = 8, 16 or 32 with
-// G * alpha <= 32): with those, the query rows that one accumulator register holds for g = 0 .. G-1
-// sit AH registers apart in the same lane, so the max over the group and the wave's softmax
+// AH = alpha / 2 selects the register path for the usual window sizes (alpha = 8, 16 or 32): with
+// those, the query rows that a lane holds for g = 0 .. G-1 sit AH accumulator registers apart (and in
+// the second row tile when G * alpha > 32), so the max over the group and the wave's softmax
 // statistics need neither LDS nor a workgroup barrier.  AH = 0 is the general path.
 template <bool HAS_Q, int MT, int AH>
 __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a) {
@@ -197,9 +197,8 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
       for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], kf, acc[mt], 0, 0, 0);
     }
     if constexpr (AH > 0) {
-      static_assert(MT == 1, "the register path covers G * alpha <= 32");
-      // accumulator element i: key = lane % 32 of this wave's 32 keys, query row g * alpha + j with
-      // g = i / AH and j = 8 * ((i % AH) / 4) + 4 * (lane / 32) + i % 4
+      // accumulator element i of row tile mt: key = lane % 32 of this wave's 32 keys, query row
+      // g * alpha + j with g = mt * (16 / AH) + i / AH and j = 8 * ((i % AH) / 4) + 4 * (lane / 32) + i % 4
       const int key = j0 + wave * 32 + lrow;
       const bool valid = key < a.n;
       float* lgt = a.logit + (int64_t)head * a.alpha * a.n_pad + key;
@@ -211,8 +210,10 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
       for (int i = 0; i < AH; ++i) {
         m[i] = acc[0][i];
 #pragma unroll
-        for (int g = 1; g < 16 / AH; ++g)
-          if (g < a.G) m[i] = fmaxf(m[i], acc[0][i + g * AH]);
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int iq = 0; iq < 16 / AH; ++iq)
+            if (mt * (16 / AH) + iq > 0 && mt * (16 / AH) + iq < a.G) m[i] = fmaxf(m[i], acc[mt][i + iq * AH]);
         m[i] *= a.scale;
         if (valid) lgt[(int64_t)(8 * (i >> 2) + 4 * khalf + (i & 3)) * a.n_pad] = m[i];
       }
@@ -292,7 +293,11 @@ void launch_variant(const PrepassArgs& a, hipStream_t stream) {
 
 int prepass_register_path(const Plan& pl) {
   const bool usual = pl.alpha == 8 || pl.alpha == 16 || pl.alpha == 32;
-  return (usual && pl.gqa_mode == 0 && pl.G * pl.alpha <= 32) ? pl.alpha / 2 : 0;
+  if (!usual || pl.gqa_mode != 0) return 0;
+  // alpha / 2, plus 100 when the G * alpha query rows need two MFMA row tiles (alpha = 32 then has
+  // G = 2, a case left to the general path)
+  if (pl.G * pl.alpha <= 32) return pl.alpha / 2;
+  return pl.alpha <= 16 ? pl.alpha / 2 + 100 : 0;
 }
 
 hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char* ws, hipStream_t stream) {
@@ -315,6 +320,8 @@ hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char
   else if (fast == 4) launch_variant<true, 1, 4>(a, stream);
   else if (fast == 8) launch_variant<true, 1, 8>(a, stream);
   else if (fast == 16) launch_variant<true, 1, 16>(a, stream);
+  else if (fast == 104) launch_variant<true, 2, 4>(a, stream);
+  else if (fast == 108) launch_variant<true, 2, 8>(a, stream);
   else if (pl.G * pl.alpha <= 32) launch_variant<true, 1, 0>(a, stream);
   else launch_variant<true, 2, 0>(a, stream);
   return hipGetLastError();

@@ -60,8 +60,9 @@ struct Plan {
 rkv_status make_plan(const rkv_params* prm, Plan* plan);
 
 // Kernel launchers (each enqueues on `stream` and returns hipGetLastError()).
-// alpha / 2 when the pre-pass merges the group's heads in registers and writes its softmax statistics
-// per 32 keys, 0 when it goes through LDS and writes them per chunk of 128 keys.
+// Non-zero (alpha / 2, plus 100 with two query row tiles) when the pre-pass merges the group's heads in
+// registers and writes its softmax statistics per 32 keys; 0 when it goes through LDS and writes them
+// per chunk of 128 keys.
 int prepass_register_path(const Plan& pl);
 hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char* ws, hipStream_t stream);
 hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stream);

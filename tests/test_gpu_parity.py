@@ -178,6 +178,8 @@ ADVERSARIAL = [
     (333, 200, 1, 1, 32, 2, 1, 0.5, 0.2),     # alpha = 32, MHA: register path, 16 values per lane
     (420, 300, 2, 1, 8, 4, 1, 0.5, 0.1),      # alpha = 8, MHA: register path with a single head per group
     (150, 100, 1, 2, 8, 4, 1, 0.5, 0.1),      # n = 142: the last chunk's third and fourth 32-key groups are empty
+    (410, 300, 2, 3, 16, 3, 1, 0.5, 0.1),     # alpha = 16, G = 3: register path over two query row tiles
+    (410, 300, 1, 8, 8, 4, 1, 0.5, 0.1),      # alpha = 8, G = 8: 64 query rows, register path over two row tiles
 ]
 
 
