@@ -281,7 +281,9 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     uint32_t mine = mine0 << (4 * half);
     const int self = row - c0;                                   // the diagonal, if it is in this tile
     if (self >= 0 && self < 32) mine &= ~(1u << self);
-    const uint32_t all = mine | (uint32_t)__shfl_xor((int)mine, 32);
+    // the two lanes of a row (l and l ^ 32) exchange their hit masks with a row swap, not through LDS
+    const auto both = __builtin_amdgcn_permlane32_swap(mine, mine, false, false);
+    const uint32_t all = both[0] | both[1];
     if (all != 0u) {
       const int room = a.beta - cnt[rt];
       uint32_t rem = all, sel = 0;
@@ -306,7 +308,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
       float s = 0.f;
 #pragma unroll
       for (int i = 15; i >= 0; --i) s += ((take0 >> (8 * (i >> 2) + (i & 3))) & 1u) ? tv[i] : 0.f;
-      s += __shfl_xor(s, 32);                    // both lanes of the row end with the same sum
+      s = pair_sum32(s);                         // both lanes of the row end with the same sum
       sub[rt] += s;
       }
       cnt[rt] += taken;
@@ -368,11 +370,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
         }
         acc[q2 & 1] = chain(kf[s % KB], res[rt]);
         // the next tile's DMA copies are spread over the steps instead of stalling the wave up front
-#ifdef EXP_PER_STEP
-        constexpr int PER_STEP = EXP_PER_STEP;
-#else
         constexpr int PER_STEP = (LOADS / NW + NS * RT - 1) / (NS * RT);
-#endif
 #pragma unroll
         for (int d = 0; d < PER_STEP; ++d)
           if (q2 * PER_STEP + d < LOADS / NW) issue_rows(ctn, buf ^ 1, q2 * PER_STEP + d, std::false_type{});
@@ -463,13 +461,9 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.part_cnt = reinterpret_cast<int*>(ws + pl.off_pcnt);
   a.part_pre = reinterpret_cast<float*>(ws + pl.off_ppre);
   a.skip_saturated = pl.skip_saturated ? 1 : 0;
-#ifdef EXP_SHAPE
-  return launch_shape<EXP_SHAPE, kPlain>(a, pl, stream);
-#else
   if (a.credit != nullptr) return launch_shape<4, 2, 128, 2, kTransposed>(a, pl, stream);
   if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit>(a, pl, stream);       // split only with beta = 1
   return launch_shape<4, 2, 128, 2, kPlain>(a, pl, stream);
-#endif
 }
 
 }  // namespace rkv
