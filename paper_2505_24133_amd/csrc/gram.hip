@@ -305,9 +305,20 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
           if ((take0 >> (8 * (i >> 2) + (i & 3))) & 1u)
             atomicAdd(cr + 8 * (i >> 2) + (i & 3), (unsigned long long)(tv[i] * r_i * 1099511627776.0f));
       } else {
+      // sum of the lane's taken similarities, most recent first: each is fetched by a four-level
+      // select on the bits of its accumulator index (usually one per row, often none in this lane)
       float s = 0.f;
-#pragma unroll
-      for (int i = 15; i >= 0; --i) s += ((take0 >> (8 * (i >> 2) + (i & 3))) & 1u) ? tv[i] : 0.f;
+      uint32_t left = take0;
+      while (left != 0u) {
+        const int pos = 31 - __clz(left);                      // bit position = 8*(i/4) + i%4
+        left &= ~(1u << pos);
+        const bool b0 = pos & 1, b1 = pos & 2, b2 = pos & 8, b3 = pos & 16;
+        const float l0 = b0 ? tv[1] : tv[0], l1 = b0 ? tv[3] : tv[2], l2 = b0 ? tv[5] : tv[4], l3 = b0 ? tv[7] : tv[6];
+        const float l4 = b0 ? tv[9] : tv[8], l5 = b0 ? tv[11] : tv[10], l6 = b0 ? tv[13] : tv[12], l7 = b0 ? tv[15] : tv[14];
+        const float m0 = b1 ? l1 : l0, m1 = b1 ? l3 : l2, m2 = b1 ? l5 : l4, m3 = b1 ? l7 : l6;
+        const float n0 = b2 ? m1 : m0, n1 = b2 ? m3 : m2;
+        s += b3 ? n1 : n0;
+      }
       s = pair_sum32(s);                         // both lanes of the row end with the same sum
       sub[rt] += s;
       }
