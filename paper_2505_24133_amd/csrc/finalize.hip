@@ -19,7 +19,11 @@ namespace {
 
 constexpr int kFinThreads = 1024;
 constexpr int kFinWaves = kFinThreads / 64;
-constexpr int kMaxPoolFloats = 16384 + 4 * (kMaxQRows + 1);   // about 65 KB of LDS for the pooling stage
+// LDS floats of the pooling stage.  With many heads two workgroups share a compute unit (74 KB each);
+// with at most one head per compute unit a workgroup takes up to 128 KB and stages more columns at once.
+constexpr int kMaxPoolFloats = 18944;
+constexpr int kMaxPoolFloatsFewHeads = 32768;
+static_assert(kMaxPoolFloats >= 16384 + 4 * (kMaxQRows + 1), "room for four columns at the largest supported window");
 
 struct FinArgs {
   const float* logit;    // [heads][rows][n_pad]
@@ -272,7 +276,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
     const int win = (a.W > 0) ? 2 * a.W : 1;
     const int halo = win - 1;
     // columns per staging block: a multiple of four, leaving room for the window behind the last one
-    const int block_cols = (min(a.pool_floats / a.pool_rows, 2 * kFinThreads) - win) & ~3;   // >= 4 (checked on the host)
+    const int block_cols = (a.pool_floats / a.pool_rows - win) & ~3;   // >= 4 (checked on the host)
     // W even: four neighbouring candidates share all but three entries of their windows, so one thread
     // serves four candidates from 16-byte LDS reads
     const bool strips = win >= 4 && (win & 3) == 0;
@@ -326,14 +330,15 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
         continue;
       }
       // eight query rows x two column slots: sixteen independent loads per thread are in flight
-      // before the first LDS store (width <= 2 * kFinThreads by the choice of block_cols)
+      // before the first LDS store
+      for (int c0 = 0; c0 < stride; c0 += 2 * kFinThreads)
       for (int j0 = 0; j0 < a.alpha; j0 += 8) {
         float v[8][2];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
 #pragma unroll
           for (int sl = 0; sl < 2; ++sl) {
-            const int c = t + sl * kFinThreads;
+            const int c = c0 + t + sl * kFinThreads;
             const int col = first + c;
             v[u][sl] = (j0 + u < a.alpha && c < width && col >= 0 && col < n)
                            ? lg[(int64_t)(j0 + u) * a.n_pad + col] : -INFINITY;      // -inf also fills width .. stride - 1
@@ -342,7 +347,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
         for (int u = 0; u < 8; ++u)
 #pragma unroll
           for (int sl = 0; sl < 2; ++sl) {
-            const int c = t + sl * kFinThreads;
+            const int c = c0 + t + sl * kFinThreads;
             if (j0 + u < a.alpha && c < stride) pool[(j0 + u) * stride + c] = v[u][sl];
           }
       }
@@ -512,9 +517,12 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   a.pool_floats = 0;
   if (mode & kModeImportance) {
     const int win = pl.W > 0 ? 2 * pl.W : 1;
-    const size_t want = (size_t)a.pool_rows * (size_t)(std::min(pl.n + 3, 2048 - win) + win);
+    const size_t want = (size_t)a.pool_rows * (size_t)(pl.n + 3 + win);
     const size_t least = (size_t)a.pool_rows * (size_t)(win + 4); // four columns per block at the very least
-    size_t pool = std::min(std::max(want, least), (size_t)kMaxPoolFloats);
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
+    const size_t cap = (pl.heads <= cus) ? kMaxPoolFloatsFewHeads : kMaxPoolFloats;
+    size_t pool = std::min(std::max(want, least), cap);
     if (pool < least) return hipErrorInvalidValue;                // rejected earlier by make_plan
     a.pool_floats = (int)pool;
     words = std::max(words, pool);
