@@ -26,6 +26,13 @@
  *   - Supported shapes: d == 128, 1 <= alpha <= 64, G * alpha <= 64, N <= 32768,
  *     pool_w <= 1000 and alpha * 2 * pool_w <= 16384,
  *     token strides multiples of 8 elements (16-byte aligned rows).
+ *   - Paged caches (optional): with page_size > 0 the k and v pointers are the bases of page pools
+ *     and token t of problem p lives in page block_table[p * table_stride + t / page_size] at slot
+ *     t % page_size:  element offset = page * k_stride_page + h * k_stride_head + slot * k_stride_token
+ *     (likewise v).  page_size is 16, 32, 64 or 128; k_stride_problem / v_stride_problem are ignored.
+ *     Every entry point that reads or writes k, v accepts this layout; k_out / v_out of rkv_compact
+ *     and rkv_compress are never paged.  The workspace then also holds a dense copy of the candidate
+ *     keys (written by the pre-pass on its single read of K, read by the similarity pass).
  */
 #ifndef RKV_H
 #define RKV_H
@@ -103,6 +110,10 @@ typedef struct {
   int64_t k_stride_problem, k_stride_head, k_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
   int64_t v_stride_problem, v_stride_head, v_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
   int64_t o_stride_problem, o_stride_head, o_stride_token;   /* of k_out and v_out; 0,0,0 = dense [P,H,budget,d] */
+  int32_t page_size;         /* 0 = contiguous caches; 16, 32, 64 or 128 tokens per page otherwise */
+  int32_t table_stride;      /* entries of block_table per problem, >= ceil(N / page_size) */
+  const int32_t* block_table;/* DEVICE pointer, int32 [P, table_stride] page indices (paged caches only) */
+  int64_t k_stride_page, v_stride_page;                      /* in elements (paged caches only) */
 } rkv_params;
 
 /* Bytes of device scratch any entry point below needs for these params. */

@@ -45,7 +45,26 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->chunks = (pl->n + kChunk - 1) / kChunk;
   pl->n_pad = pl->chunks * kChunk;
 
+  pl->paged = q.page_size != 0;
+  pl->page_shift = 0; pl->table_stride = q.table_stride; pl->block_table = q.block_table;
+  pl->kspage = q.k_stride_page; pl->vspage = q.v_stride_page;
+  if (pl->paged) {
+    if (q.page_size != 16 && q.page_size != 32 && q.page_size != 64 && q.page_size != 128) return RKV_ERR_UNSUPPORTED;
+    while ((1 << pl->page_shift) < q.page_size) ++pl->page_shift;
+    if (q.num_problems > 0 && q.block_table == nullptr) return RKV_ERR_NULL;
+    if ((int64_t)q.table_stride * q.page_size < q.n_tokens) return RKV_ERR_SHAPE;
+    auto ok = [](int64_t s) { return s > 0 && (s % 8) == 0; };
+    if (!ok(q.k_stride_page) || !ok(q.v_stride_page) || !ok(q.k_stride_token) || !ok(q.v_stride_token) ||
+        q.k_stride_token < kHeadDim || q.v_stride_token < kHeadDim || q.k_stride_token > 32768 || q.v_stride_token > 32768 ||
+        q.k_stride_head < 0 || q.v_stride_head < 0 || (q.k_stride_head % 8) != 0 || (q.v_stride_head % 8) != 0 ||
+        (q.kv_heads > 1 && (q.k_stride_head == 0 || q.v_stride_head == 0)))
+      return RKV_ERR_SHAPE;
+  }
   auto strides = [&](int64_t sp, int64_t sh, int64_t st, int64_t* op, int64_t* oh, int64_t* ot) -> bool {
+    if (pl->paged && op != &pl->osp) {                   // validated above; the problem stride is unused
+      *op = 0; *oh = sh; *ot = st;
+      return true;
+    }
     if (sp == 0 && sh == 0 && st == 0) {
       *ot = kHeadDim; *oh = (int64_t)q.n_tokens * kHeadDim; *op = *oh * q.kv_heads;
       return true;
@@ -96,6 +115,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   const size_t parts = (size_t)pl->gram_parts;
   pl->off_pcnt = take(parts > 1 ? heads * parts * np * 4 : 0);
   pl->off_ppre = take(parts > 1 ? heads * parts * np * 4 : 0);
+  pl->off_kdense = take(pl->paged ? heads * np * kHeadDim * 2 : 0);
   pl->off_idx = take(heads * (size_t)pl->budget * 4);
   pl->total = off;
   return RKV_OK;

@@ -15,7 +15,7 @@ struct AppendArgs {
   const uint16_t* v_new;
   const uint16_t* q_new;
   int H, Hq, alpha, pos, slot, kv_rows, q_rows;
-  int64_t ksp, ksh, kst, vsp, vsh, vst;
+  KvLayout kl, vl;
 };
 
 __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
@@ -25,8 +25,8 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
     const int p = row / a.H, h = row - p * a.H;
     const uint4 kx = *reinterpret_cast<const uint4*>(a.k_new + (int64_t)row * kHeadDim + c16 * 8);
     const uint4 vx = *reinterpret_cast<const uint4*>(a.v_new + (int64_t)row * kHeadDim + c16 * 8);
-    *reinterpret_cast<uint4*>(a.k_cache + p * a.ksp + h * a.ksh + (int64_t)a.pos * a.kst + c16 * 8) = kx;
-    *reinterpret_cast<uint4*>(a.v_cache + p * a.vsp + h * a.vsh + (int64_t)a.pos * a.vst + c16 * 8) = vx;
+    *reinterpret_cast<uint4*>(a.k_cache + a.kl.offset(p, h, a.pos) + c16 * 8) = kx;
+    *reinterpret_cast<uint4*>(a.v_cache + a.vl.offset(p, h, a.pos) + c16 * 8) = vx;
   } else if (row < a.kv_rows + a.q_rows) {                 // one row per (problem, query head)
     const int qr = row - a.kv_rows;
     const uint4 qx = *reinterpret_cast<const uint4*>(a.q_new + (int64_t)qr * kHeadDim + c16 * 8);
@@ -48,8 +48,7 @@ hipError_t launch_append(const Plan& pl, void* k_cache, void* v_cache, void* q_r
   a.H = pl.H; a.Hq = pl.H * pl.G; a.alpha = pl.alpha; a.pos = pos; a.slot = slot;
   a.kv_rows = pl.heads;
   a.q_rows = pl.P * pl.H * pl.G;
-  a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
-  a.vsp = pl.vsp; a.vsh = pl.vsh; a.vst = pl.vst;
+  a.kl = k_layout(pl); a.vl = v_layout(pl);
   const int threads = (a.kv_rows + a.q_rows) * 16;
   hipLaunchKernelGGL(append_kernel, dim3((threads + 255) / 256), dim3(256), 0, stream, a);
   return hipGetLastError();

@@ -25,7 +25,7 @@ struct InplaceArgs {
   uint16_t* v;
   const int32_t* kept;
   int H, N, budget, split;           // split = column slices per row (1 or 2)
-  int64_t ksp, ksh, kst, vsp, vsh, vst;
+  KvLayout kl, vl;
 };
 
 __global__ __launch_bounds__(kIpThreads) void compact_inplace_kernel(InplaceArgs a) {
@@ -35,13 +35,13 @@ __global__ __launch_bounds__(kIpThreads) void compact_inplace_kernel(InplaceArgs
   const int p = head / a.H;
   const int h = head - p * a.H;
   const bool is_v = blockIdx.y != 0;
-  const int64_t st = is_v ? a.vst : a.kst;
+  const KvLayout lay = is_v ? a.vl : a.kl;
   const int lanes = 16 / a.split;                   // 16-byte pieces of a row handled by this workgroup
   const int t = threadIdx.x;
   const int slot = t / lanes;
   const int piece = t - slot * lanes;
   const int rows_per_pass = kIpThreads / lanes;
-  uint16_t* base = (is_v ? a.v + p * a.vsp + h * a.vsh : a.k + p * a.ksp + h * a.ksh) + (slice * lanes + piece) * 8;
+  uint16_t* base = (is_v ? a.v : a.k) + (slice * lanes + piece) * 8;
   const int32_t* kept = a.kept + (int64_t)head * a.budget;
 
   if (t == 0) {
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(kIpThreads) void compact_inplace_kernel(InplaceArgs
   auto load_rows = [&](const int (&src)[kIpDepth], uint4 (&x)[kIpDepth]) {
 #pragma unroll
     for (int u = 0; u < kIpDepth; ++u)
-      x[u] = *reinterpret_cast<const uint4*>(base + (int64_t)min(max(src[u], 0), a.N - 1) * st);
+      x[u] = *reinterpret_cast<const uint4*>(base + lay.offset(p, h, min(max(src[u], 0), a.N - 1)));
   };
 
   if (r_begin >= a.budget) return;                  // nothing was evicted in front of the observation rows
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kIpThreads) void compact_inplace_kernel(InplaceArgs
 #pragma unroll
     for (int u = 0; u < kIpDepth; ++u) {
       const int r = r0 + u * rows_per_pass + slot;
-      if (r < a.budget) *reinterpret_cast<uint4*>(base + (int64_t)r * st) = cur[u];
+      if (r < a.budget) *reinterpret_cast<uint4*>(base + lay.offset(p, h, r)) = cur[u];
     }
     if (more) {
 #pragma unroll
@@ -113,8 +113,7 @@ hipError_t launch_compact_inplace(const Plan& pl, void* k, void* v, const int32_
   a.v = static_cast<uint16_t*>(v);
   a.kept = kept_idx;
   a.H = pl.H; a.N = pl.N; a.budget = pl.budget;
-  a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
-  a.vsp = pl.vsp; a.vsh = pl.vsh; a.vst = pl.vst;
+  a.kl = k_layout(pl); a.vl = v_layout(pl);
   // two 128-byte column slices per row when whole rows would leave compute units without a workgroup
   a.split = (pl.heads * 2 < 512) ? 2 : 1;
   const dim3 grid((unsigned)(pl.heads * a.split), 2);

@@ -18,7 +18,8 @@ struct GatherArgs {
   uint16_t* k_out;
   uint16_t* v_out;
   int H, N, budget, blocks_per_head;
-  int64_t ksp, ksh, kst, vsp, vsh, vst, osp, osh, ost;
+  KvLayout kl, vl;
+  int64_t osp, osh, ost;
 };
 
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
@@ -28,8 +29,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
   const int h = head - p * a.H;
   const int c16 = threadIdx.x & 15;
   const int slot = threadIdx.x >> 4;
-  const uint16_t* kb = a.k + p * a.ksp + h * a.ksh + c16 * 8;
-  const uint16_t* vb = a.v + p * a.vsp + h * a.vsh + c16 * 8;
+  const uint16_t* kb = a.k + c16 * 8;
+  const uint16_t* vb = a.v + c16 * 8;
   const int32_t* kept = a.kept + (int64_t)head * a.budget;
   uint4 kr[kRowsPerThread], vr[kRowsPerThread];
   int rows[kRowsPerThread];
@@ -41,8 +42,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a) {
     if (rows[m] < a.budget) {
       int src = kept[rows[m]];
       src = min(max(src, 0), a.N - 1);
-      kr[m] = *reinterpret_cast<const uint4*>(kb + (int64_t)src * a.kst);
-      vr[m] = *reinterpret_cast<const uint4*>(vb + (int64_t)src * a.vst);
+      kr[m] = *reinterpret_cast<const uint4*>(kb + a.kl.offset(p, h, src));
+      vr[m] = *reinterpret_cast<const uint4*>(vb + a.vl.offset(p, h, src));
     }
   }
 #pragma unroll
@@ -67,8 +68,7 @@ hipError_t launch_gather(const Plan& pl, const void* k, const void* v, const int
   a.v_out = static_cast<uint16_t*>(v_out);
   a.H = pl.H; a.N = pl.N; a.budget = pl.budget;
   a.blocks_per_head = (pl.budget + kRowsPerBlock - 1) / kRowsPerBlock;
-  a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
-  a.vsp = pl.vsp; a.vsh = pl.vsh; a.vst = pl.vst;
+  a.kl = k_layout(pl); a.vl = v_layout(pl);
   a.osp = pl.osp; a.osh = pl.osh; a.ost = pl.ost;
   const dim3 grid((unsigned)((int64_t)pl.heads * a.blocks_per_head));
   hipLaunchKernelGGL(gather_kernel, grid, dim3(kGatherThreads), 0, stream, a);

@@ -467,6 +467,11 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.credit = pl.recency_transposed ? reinterpret_cast<unsigned long long*>(ws + pl.off_credit) : nullptr;
   a.H = pl.H; a.heads = pl.heads; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks; a.beta = pl.beta;
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
+  if (pl.paged) {
+    // paged cache: the pre-pass left a dense copy of the candidate keys in the workspace
+    a.k = reinterpret_cast<const uint16_t*>(ws + pl.off_kdense);
+    a.kst = kHeadDim; a.ksh = (int64_t)pl.n_pad * kHeadDim; a.ksp = a.ksh * pl.H;
+  }
   a.T = pl.T; a.eps = pl.eps;
   a.row_blocks = 0; a.parts = pl.gram_parts;
   a.part_cnt = reinterpret_cast<int*>(ws + pl.off_pcnt);

@@ -57,6 +57,10 @@ struct PrepassArgs {
   float* logit;
   float* stats;
   int H, G, alpha, n, n_pad, chunks, items;
+  const int32_t* table;       // block table of a paged cache, or nullptr
+  int page_shift, table_stride;
+  int64_t kspage;
+  uint16_t* kdense;           // [heads][n_pad][128] dense copy of the candidate keys (paged caches), or nullptr
   int out_rows, out_groups;   // rows written per key: alpha (max over out_groups = G heads) or G*alpha (out_groups = 1)
   int64_t ksp, ksh, kst;
   float eps, scale;
@@ -66,7 +70,9 @@ struct PrepassArgs {
 // those, the query rows that a lane holds for g = 0 .. G-1 sit AH accumulator registers apart (and in
 // the second row tile when G * alpha > 32), so the max over the group and the wave's softmax
 // statistics need neither LDS nor a workgroup barrier.  AH = 0 is the general path.
-template <bool HAS_Q, int MT, int AH>
+// PAGED: the keys come from a page pool behind a block table and a dense copy of them is written for
+// the similarity pass (a separate instantiation, so that the contiguous case carries none of it).
+template <bool HAS_Q, int MT, int AH, bool PAGED>
 __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a) {
   // The logit tile reuses the key tile's LDS once every wave has read its key fragments
   // (MT * 32 rows x 136 floats <= 128 rows x 272 bytes), which lets four workgroups share a CU.
@@ -88,12 +94,24 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
     const int hd = item / a.chunks;
     const int ck = item - hd * a.chunks;
     const int pp = hd / a.H;
-    const uint16_t* kb = a.k + pp * a.ksp + (hd - pp * a.H) * a.ksh;
     // rows past n repeat row n - 1 (their r is forced to 0 below and their logits are masked)
+    if constexpr (PAGED) {
+      // paged cache: the 16 rows a thread group fetches together lie in one page (pages hold >= 16 rows)
+      const uint16_t* kb = a.k + (hd - pp * a.H) * a.ksh + c16 * 8;
+      const int32_t* tb = a.table + (int64_t)pp * a.table_stride;
+      const int mask = (1 << a.page_shift) - 1;
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      const int grow = min(ck * kChunk + m * 16 + rbase, a.n - 1);
-      dst[m] = *reinterpret_cast<const uint4*>(kb + (int64_t)grow * a.kst + c16 * 8);
+      for (int m = 0; m < 8; ++m) {
+        const int grow = min(ck * kChunk + m * 16 + rbase, a.n - 1);
+        dst[m] = *reinterpret_cast<const uint4*>(kb + tb[grow >> a.page_shift] * a.kspage + (int64_t)(grow & mask) * a.kst);
+      }
+    } else {
+      const uint16_t* kb = a.k + pp * a.ksp + (hd - pp * a.H) * a.ksh;
+#pragma unroll
+      for (int m = 0; m < 8; ++m) {
+        const int grow = min(ck * kChunk + m * 16 + rbase, a.n - 1);
+        dst[m] = *reinterpret_cast<const uint4*>(kb + (int64_t)grow * a.kst + c16 * 8);
+      }
     }
   };
   uint4 regs[8];
@@ -157,6 +175,13 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
     r8[m] = r;
 #pragma unroll
     for (int e = 0; e < 8; ++e) uacc[e] = fmaf(r, f[e], uacc[e]);
+  }
+  if constexpr (PAGED) {
+    // paged cache: the similarity pass reads the candidate keys from this dense copy
+    uint16_t* kd = a.kdense + ((int64_t)head * a.n_pad + j0 + rbase) * kHeadDim + c16 * 8;
+#pragma unroll
+    for (int m = 0; m < 8; ++m)
+      if (j0 + m * 16 + rbase < a.n) *reinterpret_cast<uint4*>(kd + (int64_t)m * 16 * kHeadDim) = regs[m];
   }
   if (c16 == 0) {
     // one lane per row writes r (0 in the padding up to n_pad) and clears the partner counter
@@ -276,17 +301,23 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
 
 // As many workgroups as stay resident at once (queried once per kernel variant), each walking over
 // its share of the items.
-template <bool HAS_Q, int MT, int AH>
-void launch_variant(const PrepassArgs& a, hipStream_t stream) {
+template <bool HAS_Q, int MT, int AH, bool PAGED>
+void launch_paged(const PrepassArgs& a, hipStream_t stream) {
   static const int res = [] {
     int per_cu = 0, dev = 0, cus = 0;
-    const void* fn = reinterpret_cast<const void*>(&prepass_kernel<HAS_Q, MT, AH>);
+    const void* fn = reinterpret_cast<const void*>(&prepass_kernel<HAS_Q, MT, AH, PAGED>);
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kPrepassThreads, 0) != hipSuccess || per_cu < 1) per_cu = 2;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
     return per_cu * cus;
   }();
   const dim3 grid((unsigned)std::min(a.items, res)), block(kPrepassThreads);
-  hipLaunchKernelGGL((prepass_kernel<HAS_Q, MT, AH>), grid, block, 0, stream, a);
+  hipLaunchKernelGGL((prepass_kernel<HAS_Q, MT, AH, PAGED>), grid, block, 0, stream, a);
+}
+
+template <bool HAS_Q, int MT, int AH>
+void launch_variant(const PrepassArgs& a, hipStream_t stream) {
+  if (a.table != nullptr) launch_paged<HAS_Q, MT, AH, true>(a, stream);
+  else launch_paged<HAS_Q, MT, AH, false>(a, stream);
 }
 
 }  // namespace
@@ -311,6 +342,9 @@ hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char
   a.stats = reinterpret_cast<float*>(ws + pl.off_stats);
   a.H = pl.H; a.G = pl.G; a.alpha = pl.alpha; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks;
   a.out_rows = pl.qrows; a.out_groups = (pl.gqa_mode == 0) ? pl.G : 1;
+  a.table = pl.paged ? pl.block_table : nullptr;
+  a.page_shift = pl.page_shift; a.table_stride = pl.table_stride; a.kspage = pl.kspage;
+  a.kdense = pl.paged ? reinterpret_cast<uint16_t*>(ws + pl.off_kdense) : nullptr;
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   a.eps = pl.eps;
   a.scale = 1.0f / sqrtf((float)kHeadDim);

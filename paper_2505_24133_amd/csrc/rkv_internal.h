@@ -20,6 +20,19 @@ constexpr int kLdsRowBytes = kRowBytes + 16;   // padded LDS row: 16-byte fragme
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
+// Where row `tok` of (problem p, KV head h) lives: contiguous caches use the three strides; paged
+// caches look the page up in the block table (rkv.h describes the layout).
+struct KvLayout {
+  const int32_t* table;        // nullptr: contiguous
+  int page_shift, table_stride;
+  int64_t sp, sh, st, spage;   // element strides: problem (contiguous only), head, token, page (paged only)
+  __device__ __forceinline__ int64_t offset(int p, int h, int tok) const {
+    if (table == nullptr) return p * sp + h * sh + (int64_t)tok * st;
+    const int page = table[(int64_t)p * table_stride + (tok >> page_shift)];
+    return page * spage + h * sh + (int64_t)(tok & ((1 << page_shift) - 1)) * st;
+  }
+};
+
 // Derived sizes and the workspace carve-up (all offsets in bytes, 256-byte aligned).
 struct Plan {
   int P, H, G, N, n, k_sel, alpha, budget, W, beta;
@@ -40,6 +53,11 @@ struct Plan {
   int64_t ksp, ksh, kst;   // key strides (elements)
   int64_t vsp, vsh, vst;   // value strides (elements)
   int64_t osp, osh, ost;   // strides of the compacted outputs (elements)
+  bool paged;              // page_size > 0
+  int page_shift, table_stride;
+  const int32_t* block_table;
+  int64_t kspage, vspage;  // page strides (elements)
+  size_t off_kdense;       // bf16  [heads][n_pad][128]       dense copy of the candidate keys (paged caches only)
   size_t off_rnorm;   // float [heads][n_pad]           1 / (|K_i| + eps), 0 for i >= n
   size_t off_upart;   // float [heads][chunks][128]     per-chunk sums of r_i K_i
   size_t off_logit;   // float [heads][qrows][n_pad]    scaled logits (group max in mode 0)
@@ -84,6 +102,13 @@ hipError_t launch_gather(const Plan& pl, const void* k, const void* v, const int
 
 // K and V compacted where they lie; kept_idx must be strictly ascending per head.
 hipError_t launch_compact_inplace(const Plan& pl, void* k, void* v, const int32_t* kept_idx, hipStream_t stream);
+
+inline KvLayout k_layout(const Plan& pl) {
+  return KvLayout{pl.paged ? pl.block_table : nullptr, pl.page_shift, pl.table_stride, pl.ksp, pl.ksh, pl.kst, pl.kspage};
+}
+inline KvLayout v_layout(const Plan& pl) {
+  return KvLayout{pl.paged ? pl.block_table : nullptr, pl.page_shift, pl.table_stride, pl.vsp, pl.vsh, pl.vst, pl.vspage};
+}
 
 hipError_t launch_append(const Plan& pl, void* k_cache, void* v_cache, void* q_ring, const void* k_new,
                          const void* v_new, const void* q_new, int pos, int slot, hipStream_t stream);

@@ -43,6 +43,8 @@ class RkvParams(ctypes.Structure):
         ("k_stride_problem", ctypes.c_int64), ("k_stride_head", ctypes.c_int64), ("k_stride_token", ctypes.c_int64),
         ("v_stride_problem", ctypes.c_int64), ("v_stride_head", ctypes.c_int64), ("v_stride_token", ctypes.c_int64),
         ("o_stride_problem", ctypes.c_int64), ("o_stride_head", ctypes.c_int64), ("o_stride_token", ctypes.c_int64),
+        ("page_size", ctypes.c_int32), ("table_stride", ctypes.c_int32), ("block_table", ctypes.c_void_p),
+        ("k_stride_page", ctypes.c_int64), ("v_stride_page", ctypes.c_int64),
     ]
 
 
@@ -104,12 +106,32 @@ class Shape:
     lam: float = 0.1
     eps: float = 1e-8
     flags: int = 0
+    # paged caches: k and v are page pools [num_pages, kv_heads, page_size, d] and block_table is a
+    # contiguous int32 GPU tensor [num_problems, table_stride] of page indices
+    page_size: int = 0
+    block_table: Optional[torch.Tensor] = None
 
     def params(self, k: Optional[torch.Tensor] = None, v: Optional[torch.Tensor] = None,
                out: Optional[torch.Tensor] = None) -> RkvParams:
         p = RkvParams(self.num_problems, self.kv_heads, self.q_heads, self.n_tokens, self.head_dim, self.alpha,
                       self.budget, self.pool_w, self.beta, self.sim_threshold, self.lam, self.eps, self.flags,
-                      0, 0, 0, 0, 0, 0, 0, 0, 0)
+                      0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, None, 0, 0)
+        if self.page_size:
+            bt = self.block_table
+            if bt is None or bt.dtype != torch.int32 or not bt.is_cuda or not bt.is_contiguous() or bt.dim() != 2 \
+                    or bt.shape[0] != self.num_problems:
+                raise ValueError("paged caches need block_table: contiguous int32 GPU tensor [num_problems, entries]")
+            p.page_size, p.table_stride, p.block_table = self.page_size, bt.shape[1], bt.data_ptr()
+            d = self.head_dim
+            natural = (self.kv_heads * self.page_size * d, self.page_size * d, d)
+            for name, t in (("k", k), ("v", v)):
+                sp, sh, st = natural if t is None else (t.stride(0), t.stride(1), t.stride(2))
+                setattr(p, f"{name}_stride_page", sp)
+                setattr(p, f"{name}_stride_head", sh)
+                setattr(p, f"{name}_stride_token", st)
+            if out is not None and not out.is_contiguous():
+                p.o_stride_problem, p.o_stride_head, p.o_stride_token = out.stride(0), out.stride(1), out.stride(2)
+            return p
         if k is not None:
             p.k_stride_problem, p.k_stride_head, p.k_stride_token = k.stride(0), k.stride(1), k.stride(2)
         if v is not None:
@@ -138,6 +160,11 @@ def _need_gpu(*tensors: torch.Tensor) -> None:
 
 
 def _check_kv(shape: Shape, t: torch.Tensor, what: str) -> None:
+    if shape.page_size:
+        if t.dim() != 4 or tuple(t.shape[1:]) != (shape.kv_heads, shape.page_size, shape.head_dim) \
+                or t.dtype != torch.bfloat16 or t.stride(3) != 1:
+            raise ValueError(f"{what} must be a bf16 page pool [pages, {shape.kv_heads}, {shape.page_size}, {shape.head_dim}]")
+        return
     want = (shape.num_problems, shape.kv_heads, shape.n_tokens, shape.head_dim)
     if tuple(t.shape) != want or t.dtype != torch.bfloat16 or t.stride(3) != 1:
         raise ValueError(f"{what} must be bf16 {want} with a contiguous last dimension, got {tuple(t.shape)} {t.dtype}")

@@ -32,9 +32,23 @@ def test_every_declared_symbol_is_exported(lib, repo_root):
     assert set(rkv.__dict__) >= set(names) - {"rkv_status_string", "rkv_compress_events"}
 
 
-def test_params_struct_layout_matches_header():
-    assert ctypes.sizeof(rkv.RkvParams) == 13 * 4 + 4 + 9 * 8      # 13 32-bit fields, pad to 8, 9 strides
-    assert rkv.RkvParams.k_stride_problem.offset == 56
+def test_params_struct_layout_matches_header(repo_root, tmp_path):
+    """The ctypes mirror against the header itself: a C program compiled from include/rkv.h prints
+    the size of rkv_params and the offset of every field."""
+    import subprocess
+    names = [f[0] for f in rkv.RkvParams._fields_]
+    c_names = ["lambda" if n == "lam" else n for n in names]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "rkv.h"\nint main(void) {\n'
+                   '  printf("%zu\\n", sizeof(rkv_params));\n'
+                   + "".join(f'  printf("%zu\\n", offsetof(rkv_params, {n}));\n' for n in c_names)
+                   + "  return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(repo_root, "include"), "-o", str(exe), str(src)], check=True)
+    out = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert out[0] == ctypes.sizeof(rkv.RkvParams)
+    assert out[1:] == [getattr(rkv.RkvParams, n).offset for n in names]
+    assert rkv.RkvParams.k_stride_problem.offset == 56 and rkv.RkvParams.page_size.offset == 56 + 9 * 8
 
 
 def shape(**kw):
@@ -79,6 +93,33 @@ def test_workspace_size_and_validation(lib):
     assert ws_status(lib, shape(pool_w=-1))[0] == rkv.RKV_ERR_PARAM
     assert ws_status(lib, shape(eps=-1.0))[0] == rkv.RKV_ERR_PARAM
     assert lib.rkv_workspace_size(None, ctypes.byref(ctypes.c_size_t(0))) == rkv.RKV_ERR_NULL
+
+
+def test_paged_cache_validation(lib):
+    """Paged layouts are checked on the host: page size, table, strides; the workspace grows by the
+    dense copy of the candidate keys."""
+    def paged(**kw):
+        p = shape().params()
+        p.page_size, p.table_stride, p.block_table = 16, 72, 0x1000       # 72 * 16 = 1152 tokens
+        p.k_stride_page = p.v_stride_page = 8 * 16 * 128
+        p.k_stride_head = p.v_stride_head = 16 * 128
+        p.k_stride_token = p.v_stride_token = 128
+        for k_, v_ in kw.items():
+            setattr(p, k_, v_)
+        n = ctypes.c_size_t(0)
+        return lib.rkv_workspace_size(ctypes.byref(p), ctypes.byref(n)), n.value
+    ok, nbytes = paged()
+    assert ok == rkv.RKV_OK and nbytes >= ws_status(lib, shape())[1] + 2 * 8 * 1144 * 256   # + bf16 [heads][n][128]
+    assert paged(page_size=24)[0] == rkv.RKV_ERR_UNSUPPORTED
+    assert paged(page_size=256)[0] == rkv.RKV_ERR_UNSUPPORTED
+    assert paged(block_table=None)[0] == rkv.RKV_ERR_NULL
+    assert paged(table_stride=71)[0] == rkv.RKV_ERR_SHAPE                  # 71 pages hold 1136 < 1152 tokens
+    assert paged(k_stride_page=0)[0] == rkv.RKV_ERR_SHAPE
+    assert paged(v_stride_token=64)[0] == rkv.RKV_ERR_SHAPE
+    assert paged(k_stride_head=0)[0] == rkv.RKV_ERR_SHAPE                  # several heads need a head stride
+    assert paged(k_stride_token=132)[0] == rkv.RKV_ERR_SHAPE               # rows must stay 16-byte aligned
+    for ps in (16, 32, 64, 128):
+        assert paged(page_size=ps, table_stride=(1152 + ps - 1) // ps)[0] == rkv.RKV_OK
 
 
 def test_null_and_workspace_errors_return_before_any_launch(lib):

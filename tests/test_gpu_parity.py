@@ -718,6 +718,89 @@ def test_hip_graph_replays_match_eager():
         assert torch.equal(got[0], ko2) and torch.equal(got[1], vo2), f"replay {r}: compacted rows differ"
 
 
+def _paged_copy(rng, dense, page_size, spare=3):
+    """dense [P, H, N, d] -> (pool [pages, H, page_size, d], table [P, ceil(N / page_size)]): pages are
+    dealt in a random order, `spare` unused pages hold a marker, the tail of the last page of a
+    problem is left as marker too."""
+    P, H, N, d = dense.shape
+    per = (N + page_size - 1) // page_size
+    order = rng.permutation(P * per + spare)
+    table = order[:P * per].reshape(P, per).astype(np.int32)
+    pool = np.full((P * per + spare, H, page_size, d), 0x7FC0, dtype=np.uint16)      # bf16 NaN marker
+    for p in range(P):
+        for b in range(per):
+            rows = dense[p, :, b * page_size:(b + 1) * page_size]
+            pool[table[p, b], :, :rows.shape[1]] = rows
+    return pool, table
+
+
+def _unpage(pool, table, N):
+    P, per = table.shape
+    ps = pool.shape[2]
+    return np.concatenate([pool[table[:, b]] for b in range(per)], axis=2)[:, :, :N]
+
+
+@pytest.mark.parametrize("page_size", [16, 32, 64, 128])
+def test_paged_cache_equals_contiguous(page_size):
+    """The same K/V held in a page pool behind a block table: every entry point gives bit for bit
+    what it gives on the contiguous cache (which the other tests check against the oracle), the
+    in-place form leaves the kept rows in the first pages of each problem and touches nothing else,
+    and a row appended through the table lands in its page."""
+    w = synth.scaled(synth.CONFIGS["cfg1_tiny"], num_problems=3, n_tokens=363, budget=250, kv_heads=2, q_heads=8)
+    q, k, v = synth.make_batch(w)
+    rng = np.random.default_rng(page_size)
+    kp, table = _paged_copy(rng, k, page_size)
+    vp, _ = _paged_copy(np.random.default_rng(page_size), v, page_size)              # same table (same seed)
+    shp = shape_of(w, 3)
+    qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    say(f"paged cache, page_size={page_size}: dense reference run")
+    st, ko, vo, idx, score = rkv.rkv_compress(shp, qd, kd, vd, want_idx=True, want_score=True)
+    imp = rkv.rkv_score_importance(shp, qd, kd)
+    red, msim = rkv.rkv_score_redundancy(shp, kd, want_mean_sim=True)
+    torch.cuda.synchronize()
+    run_fused(w, q, k, v, [(1, 0)], f"paged{page_size}_dense_reference")
+    import dataclasses
+    pshp = dataclasses.replace(shp, page_size=page_size, block_table=torch.from_numpy(table).cuda())
+    kpd, vpd = dev_bf16(kp), dev_bf16(vp)
+    say(f"paged cache, page_size={page_size}: paged entry points")
+    st2, ko2, vo2, idx2, score2 = rkv.rkv_compress(pshp, qd, kpd, vpd, want_idx=True, want_score=True)
+    imp2 = rkv.rkv_score_importance(pshp, qd, kpd)
+    red2, msim2 = rkv.rkv_score_redundancy(pshp, kpd, want_mean_sim=True)
+    ko3, vo3 = rkv.rkv_compact(pshp, kpd, vpd, idx2)
+    torch.cuda.synchronize()
+    assert st2 == rkv.RKV_OK
+    assert torch.equal(idx, idx2) and torch.equal(score, score2)
+    assert torch.equal(ko, ko2) and torch.equal(vo, vo2) and torch.equal(ko, ko3) and torch.equal(vo, vo3)
+    assert torch.equal(imp, imp2) and torch.equal(red, red2) and torch.equal(msim, msim2)
+    np.testing.assert_array_equal(host_bits(kpd), kp)                                 # inputs untouched
+    # in place: kept rows move to the front of each problem's token order
+    say(f"paged cache, page_size={page_size}: in place")
+    st3, idx3, _ = rkv.rkv_compress_inplace(pshp, qd, kpd, vpd)
+    torch.cuda.synchronize()
+    assert st3 == rkv.RKV_OK and torch.equal(idx3, idx)
+    k_after, v_after = host_bits(kpd), host_bits(vpd)
+    np.testing.assert_array_equal(_unpage(k_after, table, w.n_tokens)[:, :, :w.budget], host_bits(ko))
+    np.testing.assert_array_equal(_unpage(v_after, table, w.n_tokens)[:, :, :w.budget], host_bits(vo))
+    np.testing.assert_array_equal(_unpage(k_after, table, w.n_tokens)[:, :, w.budget:], k[:, :, w.budget:])
+    used = np.zeros(kp.shape[0], dtype=bool)
+    used[table.ravel()] = True
+    np.testing.assert_array_equal(k_after[~used], kp[~used])                          # spare pages untouched
+    last = table[:, -1]
+    tail = w.n_tokens - (table.shape[1] - 1) * page_size
+    np.testing.assert_array_equal(k_after[last][:, :, tail:], kp[last][:, :, tail:])  # slots past N untouched
+    # append through the table
+    newk = dev_bf16(synth.f32_to_bf16_bits(rng.standard_normal((3, 2, 128)).astype(np.float32)))
+    newv = dev_bf16(synth.f32_to_bf16_bits(rng.standard_normal((3, 2, 128)).astype(np.float32)))
+    newq = dev_bf16(synth.f32_to_bf16_bits(rng.standard_normal((3, 8, 128)).astype(np.float32)))
+    qring = qd.clone()
+    pos = w.budget + 1
+    rkv.rkv_cache_append(pshp, kpd, vpd, qring, newk, newv, newq, pos, 5)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(_unpage(host_bits(kpd), table, w.n_tokens)[:, :, pos], host_bits(newk))
+    np.testing.assert_array_equal(_unpage(host_bits(vpd), table, w.n_tokens)[:, :, pos], host_bits(newv))
+    np.testing.assert_array_equal(host_bits(qring)[:, :, 5], host_bits(newq))
+
+
 def test_shared_workspace_across_shapes():
     """One oversized workspace reused by calls of different shapes: nothing read is left over from
     an earlier call."""
