@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from dataclasses import dataclass
+from dataclasses import dataclass, field
 from typing import Optional, Tuple
 
 import torch
@@ -109,7 +109,7 @@ class Shape:
     # paged caches: k and v are page pools [num_pages, kv_heads, page_size, d] and block_table is a
     # contiguous int32 GPU tensor [num_problems, table_stride] of page indices
     page_size: int = 0
-    block_table: Optional[torch.Tensor] = None
+    block_table: Optional[torch.Tensor] = field(default=None, compare=False, repr=False)
 
     def params(self, k: Optional[torch.Tensor] = None, v: Optional[torch.Tensor] = None,
                out: Optional[torch.Tensor] = None) -> RkvParams:
