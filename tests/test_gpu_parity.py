@@ -180,6 +180,10 @@ ADVERSARIAL = [
     (150, 100, 1, 2, 8, 4, 1, 0.5, 0.1),      # n = 142: the last chunk's third and fourth 32-key groups are empty
     (410, 300, 2, 3, 16, 3, 1, 0.5, 0.1),     # alpha = 16, G = 3: register path over two query row tiles
     (410, 300, 1, 8, 8, 4, 1, 0.5, 0.1),      # alpha = 8, G = 8: 64 query rows, register path over two row tiles
+    (2300, 2000, 1, 4, 8, 1000, 1, 0.5, 0.1),  # the widest pooling window (2W = 2000): few columns per staging block
+    (1100, 900, 1, 1, 64, 120, 1, 0.5, 0.1),   # alpha = 64 with 2W = 240: 56 columns per staging block, 19 blocks
+    (900, 700, 1, 2, 8, 3, 1, 0.5, 0.1),       # W odd: the pooling window is not a multiple of four entries
+    (5000, 4600, 2, 4, 8, 4, 1, 0.5, 0.1),     # two heads of 4992 candidates: one large staging block each
 ]
 
 
@@ -201,6 +205,7 @@ VARIANT_SHAPES = [
     (2100, 1900, 4, 2, 8, 4, 2, 0.5, 0.1),     # more than one staging block
     (260, 250, 5, 1, 4, 0, 0, 0.5, 0.5),       # no pooling, five heads averaged
     (390, 257, 2, 2, 32, 2, 1, 0.4, 0.2),      # G * alpha = 64 logit rows per head
+    (600, 500, 1, 1, 63, 128, 1, 0.5, 0.1),    # (alpha + 1) * 2W = 16384: the largest window the mean-then-pool order takes
 ]
 VARIANT_FLAGS = {"mean_then_pool": 2, "shared": 4, "both": 6, "gqa_softmax_max": 8, "gqa_softmax_mean": 16,
                  "gqa_softmax_max_mean_then_pool_shared": 14, "gqa_softmax_mean_mean_then_pool": 18,
