@@ -248,6 +248,7 @@ def main() -> int:
                    "n_tokens": w.n_tokens, "budget": w.budget, "alpha": w.alpha, "head_dim": d,
                    "pool_w": w.pool_w, "beta": w.beta, "sim_threshold": w.sim_threshold, "lambda": w.lam},
         "cached_tokens_scored_per_sec": w.num_problems * n / (ms_per_step * 1e-3),
+        "cached_head_tokens_scored_per_sec": heads * n / (ms_per_step * 1e-3),
         "ms_per_step_with_stage_events": ms_per_step_events,
         "stages": {s: {kk: float(vv) for kk, vv in st.items()} for s, st in stages.items()},
         "roofline": roofline,
