@@ -39,6 +39,7 @@ struct GramArgs {
   float* part_pre;              // [heads][parts][n_pad] their sum
   int H, heads, n, n_pad, chunks, beta, skip_saturated;
   int row_blocks, parts;        // workgroups per head = row_blocks * parts
+  int tail_last;                // narrow last row blocks are listed after all other workgroups
   int64_t ksp, ksh, kst;
   float T, eps;
 };
@@ -91,18 +92,32 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   constexpr int OFF_RJ = OFF_TILE + 2 * TILE_SPAN;
 
   // Workgroups are dealt round-robin to the 8 XCDs; give every XCD whole heads so that a head's
-  // keys are fetched into one L2 only.
-  // Workgroups are dealt round-robin to the 8 XCDs; give every XCD whole heads so that a head's
-  // keys are fetched into one L2 only.  A head's workgroups (row block x column part) are adjacent.
+  // keys are fetched into one L2 only.  A head's workgroups (row block x column part) are adjacent,
+  // except that narrow last row blocks (at most NW * 32 rows, about half the lifetime of the others)
+  // come after all the others: the launch then ends with short workgroups instead of full-length ones.
   const int b = blockIdx.x;
   const int xcd = b & 7;
-  const int q = b >> 3;
+  int q = b >> 3;
   const int parts = (VARIANT == kSplit) ? a.parts : 1;
-  const int per_head = a.row_blocks * parts;
-  const int head = (q / per_head) * 8 + xcd;
-  const int rem = q % per_head;
-  const int rb = rem / parts;
-  const int part = rem - rb * parts;
+  const int head_groups = (a.heads + 7) >> 3;
+  const bool tail_last = (VARIANT != kSplit) && (WPS < 3) && a.tail_last != 0;
+  int head, rb, part;
+  if (!tail_last) {
+    const int per_head = a.row_blocks * parts;
+    head = (q / per_head) * 8 + xcd;
+    const int rem = q % per_head;
+    rb = rem / parts;
+    part = rem - rb * parts;
+  } else if (q < head_groups * (a.row_blocks - 1)) {
+    head = (q / (a.row_blocks - 1)) * 8 + xcd;
+    rb = q % (a.row_blocks - 1);
+    part = 0;
+  } else {
+    q -= head_groups * (a.row_blocks - 1);
+    head = q * 8 + xcd;
+    rb = a.row_blocks - 1;
+    part = 0;
+  }
   if (head >= a.heads) return;
 
   const int t = threadIdx.x;
@@ -112,10 +127,20 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   const int half = lane >> 5;
   const int p = head / a.H;
   const int h = head - p * a.H;
-  const uint16_t* kbase = a.k + p * a.ksp + h * a.ksh;
+  // the head's key base is workgroup-uniform; pinning it to scalar registers here keeps every DMA
+  // address computation below on the scalar unit
+  const uint64_t kb64 = (uint64_t)(uintptr_t)(a.k + p * a.ksp + h * a.ksh);
+  const uint16_t* kbase = reinterpret_cast<const uint16_t*>(
+      ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(kb64 >> 32)) << 32) |
+      (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)kb64));
   const float* rn = a.rnorm + (int64_t)head * a.n_pad;
   const int n = a.n;
-  const int i0 = rb * BM + wave * (RT * 32);
+  // A last row block with at most NW * 32 rows is "narrow": every wave takes one row tile of it instead
+  // of two waves taking two each, and the scan below runs with one chain per subtile, so the workgroup
+  // lives about half as long.  The second row tile of a wave then stands for rows past n.
+  const bool narrow = (KB == 2) && (n - rb * BM <= NW * 32);
+  const int i0 = rb * BM + wave * (narrow ? 32 : RT * 32);
+  const int tile_rows = narrow ? (1 << 20) : 32;     // row distance between a wave's row tiles
   const bool active = i0 < n;                        // wave-uniform: does this wave own any candidate row?
   const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)gram_lds);   // LDS byte address of the dynamic segment
   const uint32_t row_bytes = (uint32_t)a.kst * 2u;
@@ -171,7 +196,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   int cnt[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const int rowc = min(i0 + rt * 32 + lrow, n - 1);
+    const int rowc = min(i0 + rt * tile_rows + lrow, n - 1);
     rni[rt] = rn[rowc];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
@@ -199,7 +224,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   }
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const int row = i0 + rt * 32 + lrow;
+    const int row = i0 + rt * tile_rows + lrow;
     thr[rt] = (row < n && a.beta > 0) ? a.T / rni[rt] : INFINITY;
     sub[rt] = 0.f;
     cnt[rt] = 0;
@@ -268,7 +293,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   };
   // Rare case: the row's hits in this tile, ranked by key (descending); forgive the first ones.
   auto tile_hits = [&](const f32x16& acc, const float (&rj)[16], int rt, int c0) {
-    const int row = i0 + rt * 32 + lrow;
+    const int row = i0 + rt * tile_rows + lrow;
     // Accumulator element i holds key c0 + 8*(i/4) + 4*half + i%4.  Masks are built with the bit
     // positions of half 0 (compile-time constants) and shifted by 4*half once.
     float tv[16];
@@ -336,7 +361,10 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     }
   };
 
-  // ---- stream the tiles, most recent first
+  // ---- stream the tiles, most recent first; RTE = row tiles of the wave that take part (RT, or 1 in a
+  // narrow row block)
+  auto scan = [&](auto rte) __attribute__((always_inline)) {
+  constexpr int RTE = decltype(rte)::value;
   for (int it = 0; it < nct; ++it) {
     const int ct = ct_hi - 1 - it;
     const int buf = it & 1;
@@ -362,17 +390,18 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     f32x16 acc[2];
     read_k(kf[(NS - 1) % KB], tile, NS - 1);
     read_rj(rj[(NS - 1) % KB], rjs, NS - 1);
-    // software pipeline over the NS * RT tiles of this iteration: chain(q) with test(q - 1)
+    // software pipeline over the NS * RTE tiles of this iteration: chain(q) with test(q - 1)
 #pragma unroll
-    for (int q2 = 0; q2 <= NS * RT; ++q2) {
+    for (int q2 = 0; q2 <= NS * RTE; ++q2) {
       if (q2 > 0) __builtin_amdgcn_sched_barrier(0);
-      if (q2 < NS * RT) {
-        const int s = NS - 1 - q2 / RT, rt = q2 % RT;
+      if (q2 < NS * RTE) {
+        const int s = NS - 1 - q2 / RTE, rt = q2 % RTE;
         if constexpr (KB == 2) {
           // prefetch the next subtile: its key fragments replace those of subtile s + 1 (all chains on
           // them are issued); its r_j replace those of s + 1 one step later, after that subtile's last test
           if (rt == 0 && s > 0) read_k(kf[(s - 1) & 1], tile, s - 1);
-          if (rt == 1 && s > 0) read_rj(rj[(s - 1) & 1], rjs, s - 1);
+          if (RTE > 1 && rt == 1 && s > 0) read_rj(rj[(s - 1) & 1], rjs, s - 1);
+          if (RTE == 1 && q2 == 0 && s > 0) read_rj(rj[(s - 1) & 1], rjs, s - 1);   // single row tile: the rest follow the tests
         } else {
           // single set: fetch this subtile's fragments now (the previous subtile's chains are issued)
           // and its r_j one step later (the previous subtile's last test ran in the step before)
@@ -381,17 +410,21 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
         }
         acc[q2 & 1] = chain(kf[s % KB], res[rt]);
         // the next tile's DMA copies are spread over the steps instead of stalling the wave up front
-        constexpr int PER_STEP = (LOADS / NW + NS * RT - 1) / (NS * RT);
+        constexpr int PER_STEP = (LOADS / NW + NS * RTE - 1) / (NS * RTE);
 #pragma unroll
         for (int d = 0; d < PER_STEP; ++d)
           if (q2 * PER_STEP + d < LOADS / NW) issue_rows(ctn, buf ^ 1, q2 * PER_STEP + d, std::false_type{});
       }
       if (q2 > 0) {
         const int qp = q2 - 1;
-        const int sp = NS - 1 - qp / RT, rtp = qp % RT;
+        const int sp = NS - 1 - qp / RTE, rtp = qp % RTE;
         const float m = tile_max(acc[qp & 1], rj[sp % KB]);
-        if (q2 < NS * RT) interleave();
+        if (q2 < NS * RTE) interleave();
         if (__any(m > thr[rtp])) tile_hits(acc[qp & 1], rj[sp % KB], rtp, ct * TC + sp * 32);
+        if constexpr (KB == 2 && RTE == 1) {
+          // subtile sp's test is done: its r_j registers take those of subtile sp - 2
+          if (sp >= 2) read_rj(rj[sp & 1], rjs, sp - 2);
+        }
       }
     }
     } else {
@@ -413,12 +446,15 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
       __syncthreads();
     }
   }
+  };   // scan
+  if (narrow) scan(std::integral_constant<int, 1>{});
+  else scan(std::integral_constant<int, RT>{});
 
   // ---- closed-form row sums minus the forgiven similarities
   if (half == 0) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const int row = i0 + rt * 32 + lrow;
+      const int row = i0 + rt * tile_rows + lrow;
       if (row < n) {
         const float r = rn[row];
         const float self = 1.0f - a.eps * r;               // r_i |K_i| = 1 - eps r_i
@@ -451,6 +487,11 @@ hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   static_assert(BM == kGramRows && TC == kGramTile, "the plan's split of the similarity pass assumes this shape");
   const int head_groups = (pl.heads + 7) / 8;
   a.row_blocks = (pl.n + BM - 1) / BM;
+  // Narrow last row blocks live about half as long as the others.  Listing them last makes the launch end
+  // with short workgroups; it also separates them from their head's other workgroups (their keys are then
+  // fetched again), which only pays while the launch is a few rounds of workgroups long.
+  const bool narrow_tail = a.row_blocks > 1 && pl.n - (a.row_blocks - 1) * BM <= NW * 32;
+  a.tail_last = (narrow_tail && (int64_t)pl.heads * a.row_blocks <= 8192) ? 1 : 0;
   const dim3 grid((unsigned)((int64_t)head_groups * 8 * a.row_blocks * a.parts));
   hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS, VARIANT>), grid, dim3(NW * 64), lds, stream, a);
   return hipGetLastError();
