@@ -487,11 +487,12 @@ hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   static_assert(BM == kGramRows && TC == kGramTile, "the plan's split of the similarity pass assumes this shape");
   const int head_groups = (pl.heads + 7) / 8;
   a.row_blocks = (pl.n + BM - 1) / BM;
-  // Narrow last row blocks live about half as long as the others.  Listing them last makes the launch end
-  // with short workgroups; it also separates them from their head's other workgroups (their keys are then
-  // fetched again), which only pays while the launch is a few rounds of workgroups long.
+  // Narrow last row blocks live about two thirds as long as the others.  Listing them last makes the
+  // launch end with short workgroups; it also separates them from their head's other workgroups, so
+  // their head's keys are fetched from HBM a second time.  That trade only pays while the launch is
+  // two or three rounds of workgroups long (the last round is then a large share of it and HBM idles).
   const bool narrow_tail = a.row_blocks > 1 && pl.n - (a.row_blocks - 1) * BM <= NW * 32;
-  a.tail_last = (narrow_tail && (int64_t)pl.heads * a.row_blocks <= 8192) ? 1 : 0;
+  a.tail_last = (narrow_tail && (int64_t)pl.heads * a.row_blocks <= 2048) ? 1 : 0;
   const dim3 grid((unsigned)((int64_t)head_groups * 8 * a.row_blocks * a.parts));
   hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS, VARIANT>), grid, dim3(NW * 64), lds, stream, a);
   return hipGetLastError();
