@@ -551,3 +551,40 @@ def test_batched_compress_head_mapping():
     one = O.compress_head(q[0, G:2 * G], k[0, 1], v[0, 1], prm)
     np.testing.assert_array_equal(res[(0, 1)]["kept"], one["kept"])
     assert res[(0, 1)]["kept"].shape == (w.budget,)
+
+
+def test_compress_head_variant_fields_reach_their_steps():
+    """Every variant field of Params changes the step it names inside compress_head (the steps
+    themselves are pinned above); checked through invariants that tell the readings apart."""
+    # keep-recent rule, other direction: three exact copies p1 < p2 < p3 among orthogonal keys, beta = 1.
+    # Literal rule: every copy loses one of its two unit similarities -> 1/n each.  Other direction: p1
+    # and p2 both zero their entry in p3's row, p3 zeroes its entry in p2's row -> (2, 1, 0) / n.
+    pos, n, (qb, kb, vb) = _dup_case(3, 1)
+    base = dict(alpha=2, budget=n - 2 + 2, pool_w=0, beta=1, lam=0.0)
+    lit = O.compress_head(qb, kb, vb, O.Params(**base))["mean_sim"]
+    oth = O.compress_head(qb, kb, vb, O.Params(recency_transposed=True, **base))["mean_sim"]
+    np.testing.assert_allclose(lit[pos], np.array([1.0, 1.0, 1.0]) / n, rtol=1e-6)
+    np.testing.assert_allclose(oth[pos], np.array([2.0, 1.0, 0.0]) / n, rtol=1e-6, atol=1e-12)
+
+    # pooling order: the mean of row maxima dominates the maximum of the row mean, strictly somewhere
+    qb, kb, vb = _head_inputs(21, G=2, alpha=4)
+    prm = dict(alpha=4, budget=40, pool_w=3, lam=0.1)
+    I_eq4 = O.compress_head(qb, kb, vb, O.Params(**prm))["importance"]
+    I_alg = O.compress_head(qb, kb, vb, O.Params(pool_after_mean=True, **prm))["importance"]
+    assert np.all(I_eq4 >= I_alg - 1e-15) and np.any(I_eq4 > I_alg * (1 + 1e-9))
+    q, kc = O.decode_bf16(qb), O.decode_bf16(kb[:68])
+    np.testing.assert_array_equal(I_alg, O.importance_mean_then_pool(q, kc, 3))
+    np.testing.assert_array_equal(I_eq4, O.importance(q, kc, 3))
+
+    # group merge: without pooling the importance sums to 1 when the merged rows are distributions
+    # (max of logits, mean of softmaxes) and exceeds 1 for the un-normalised max of softmaxes; both are
+    # bounded by the max of softmaxes element by element (the pooled logits' normaliser is at least
+    # every head's own)
+    prm = dict(alpha=4, budget=40, pool_w=0, lam=0.1)
+    I = {g: O.compress_head(qb, kb, vb, O.Params(gqa=g, **prm))["importance"]
+         for g in ("max_logits", "softmax_max", "softmax_mean")}
+    assert abs(I["max_logits"].sum() - 1) < 1e-12 and abs(I["softmax_mean"].sum() - 1) < 1e-12
+    assert I["softmax_max"].sum() > 1 + 1e-3
+    assert np.all(I["softmax_mean"] <= I["softmax_max"] + 1e-15)
+    assert np.all(I["max_logits"] <= I["softmax_max"] + 1e-15)
+    assert not np.allclose(I["max_logits"], I["softmax_mean"], rtol=1e-3)
