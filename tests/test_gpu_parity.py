@@ -516,6 +516,27 @@ def test_largest_supported_cache_sampled_rows():
     w = synth.Workload("max", 1, 1, 4, N, budget, alpha=alpha, seed=91, recipe="clusters", n_clusters=4096,
                        cluster_sigma=0.25, pool_w=4, beta=1, sim_threshold=0.8, lam=0.1)
     q, k, v = synth.make_batch(w)
+    # Planted rows that tell "most recent partner" from any other choice: token i is an exact copy of an
+    # old token (similarity 1) and has a loosely similar partner (cosine 0.81) at a larger index, many
+    # column tiles away.  The rule forgives the recent, loose partner; forgiving the old exact copy
+    # instead would move the mean similarity by 0.19 / n.  The planted direction is orthogonal to the sum
+    # of all normalised keys, so the row's mean similarity is small and the tolerance below stays near
+    # its absolute part, a third of that shift.
+    rng = np.random.default_rng(92)
+    kall = O.decode_bf16(k[0, 0][:w.n_cand])
+    usum = (kall / np.sqrt((kall * kall).sum(1, keepdims=True))).sum(0)
+    usum /= np.linalg.norm(usum)
+    planted = []
+    for (i, j_old, j_recent) in [(15000, 200, 31000), (25000, 100, 25900), (7, 3, 32500)]:
+        base = rng.standard_normal(128)
+        base -= (base @ usum) * usum
+        noise = rng.standard_normal(128)
+        noise -= (noise @ usum) * usum
+        noise -= (noise @ base) / (base @ base) * base
+        noise *= np.linalg.norm(base) / np.linalg.norm(noise)
+        k[0, 0, i] = k[0, 0, j_old] = synth.f32_to_bf16_bits(base.astype(np.float32))
+        k[0, 0, j_recent] = synth.f32_to_bf16_bits((base + 0.72 * noise).astype(np.float32))
+        planted.append(i)
     shp = shape_of(w, 1)
     qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
     say("max size: rkv_score_redundancy + rkv_compress N=32768")
@@ -524,7 +545,7 @@ def test_largest_supported_cache_sampled_rows():
     torch.cuda.synchronize()
     n = w.n_cand
     kc = O.decode_bf16(k[0, 0][:n])
-    rows = [0, 1, 127, 128, 4095, 9999, 16384, 20000, 32000, n - 129, n - 2, n - 1]
+    rows = [0, 1, 127, 128, 4095, 9999, 16384, 20000, 32000, n - 129, n - 2, n - 1] + planted
     ref = O.mean_similarity_rows(kc, rows, float(np.float32(w.sim_threshold)), w.beta, w.eps)
     got = msim[0, 0].cpu().numpy()[rows]
     # a sampled row is exempt only if one of its similarities sits within the fp32 band around T
@@ -532,7 +553,12 @@ def test_largest_supported_cache_sampled_rows():
     for r_i, (i, g, e) in enumerate(zip(rows, got, ref)):
         srow = kbar @ kbar[i]; srow[i] = 0.0
         if np.any(np.abs(srow - w.sim_threshold) <= Hp.SIM_BAND):
+            assert i not in planted
             continue
+        if i in planted:                                   # the planted structure is what it claims to be
+            hits = np.nonzero(srow > w.sim_threshold)[0]
+            assert len(hits) == 2 and srow[hits[0]] > 0.999 and 0.805 < srow[hits[1]] < 0.82 and hits[1] > i
+            assert (srow[hits[0]] - srow[hits[1]]) / n > 2.5 * (2e-6 + 1e-3 * abs(e))
         assert abs(g - e) <= 2e-6 + 1e-3 * abs(e), f"row {i}: gpu {g} oracle {e}"
     z = score[0, 0].cpu().numpy()
     kept = idx[0, 0].cpu().numpy()
