@@ -69,8 +69,8 @@ def cpu_baseline(w, q, k, v, seconds: float):
 def other_modes(torch, rkv, synth, w, shp, qd, kd, vd, ws, ko, vo, idx, reps=50):
     """The same workload launched in other ways, for context next to the headline figure (ms per step):
     one call per layer back to back on one stream (eager, and replayed from a HIP graph), a high
-    threshold at which only true near-duplicates count as similar, and attention-only eviction
-    (lambda = 1, no similarity pass)."""
+    threshold at which only true near-duplicates count as similar, attention-only eviction
+    (lambda = 1, no similarity pass), the exact shortcut of the similarity pass, and in-place compaction."""
     import dataclasses
 
     def timed(fn):
@@ -105,6 +105,24 @@ def other_modes(torch, rkv, synth, w, shp, qd, kd, vd, ws, ko, vo, idx, reps=50)
     for name, change in (("sim_threshold_0.95_ms", {"sim_threshold": 0.95}), ("attention_only_lambda_1_ms", {"lam": 1.0})):
         alt = dataclasses.replace(shp, **change)
         res[name] = timed(lambda: rkv.rkv_compress(alt, qd, kd, vd, ws=ws, k_out=ko, v_out=vo, kept_idx=idx))
+    # the exact shortcut of the similarity pass (a row that has met its beta partners is left alone;
+    # same results, data-dependent time: with these keys nearly every row is done after one column tile)
+    alt = dataclasses.replace(shp, flags=shp.flags | rkv.RKV_FLAG_SKIP_SATURATED)
+    res["skip_saturated_ms"] = timed(lambda: rkv.rkv_compress(alt, qd, kd, vd, ws=ws, k_out=ko, v_out=vo, kept_idx=idx))
+    # compaction inside the cache allocation instead of into a second one (copies of the caches: the
+    # call overwrites them; only rows behind the first evicted one move)
+    kc, vc = kd.clone(), vd.clone()
+    spans = []
+    for _ in range(5 + reps):
+        kc.copy_(kd)
+        vc.copy_(vd)                                 # every call sees the same cache contents
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        rkv.rkv_compress_inplace(shp, qd, kc, vc, ws=ws, kept_idx=idx)
+        t1.record()
+        spans.append((t0, t1))
+    torch.cuda.synchronize()
+    res["inplace_ms"] = sum(a.elapsed_time(b) for a, b in spans[5:]) / reps
     return {k_: float(v_) for k_, v_ in res.items()}
 
 
