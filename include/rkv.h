@@ -58,8 +58,9 @@ typedef enum {
 /*
  * rkv_params.flags.  RKV_FLAG_SKIP_SATURATED: exact shortcut of the redundancy pass.  A token whose
  * `beta` most recent similar tokens have been found cannot change any more (Sec. 3.3 zeroes only those
- * beta entries), so a wave whose rows are all in that state stops forming similarity tiles.  Results
- * are bit-identical to flags = 0; only the amount of matrix work differs (data dependent).
+ * beta entries), so rows in that state take no further part in the pass and the rows still open are
+ * gathered into fewer waves as their number falls.  Results are bit-identical to flags = 0; only the
+ * amount of matrix work differs (data dependent).
  */
 #define RKV_FLAG_SKIP_SATURATED 1u
 /*

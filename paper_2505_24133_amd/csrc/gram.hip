@@ -37,7 +37,7 @@ struct GramArgs {
   unsigned long long* credit;   // [heads][n_pad] or nullptr: forgiven similarities charged to the partner
   int* part_cnt;                // [heads][parts][n_pad] hits per row found by one column part
   float* part_pre;              // [heads][parts][n_pad] their sum
-  int H, heads, n, n_pad, chunks, beta, skip_saturated;
+  int H, heads, n, n_pad, chunks, beta;
   int row_blocks, parts;        // workgroups per head = row_blocks * parts
   int tail_last;                // narrow last row blocks are listed after all other workgroups
   int64_t ksp, ksh, kst;
@@ -73,8 +73,14 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t l
 //   kSplit       the scan is shared by several workgroups, each reports what it found (beta = 1)
 //   kTransposed  forgiven similarities are charged to the recent partner's counter
 enum GramVariant : int { kPlain = 0, kSplit = 1, kTransposed = 2 };
+// SKIP adds the exact shortcut: a row that has met beta partners can gain nothing from the columns still
+// to come, so a wave whose rows are all done stops forming tiles, a workgroup whose rows are all done
+// leaves the scan, and when the rows still open fit into half as many row tiles as are in use they are
+// gathered into the first waves (one row tile each) and the other waves only help copying tiles.
 
-template <int NW, int RT, int TC, int WPS, int VARIANT>
+constexpr int kCompactBytes = 3072;             // SKIP: open-row counts of the waves and the records of moved rows
+
+template <int NW, int RT, int TC, int WPS, int VARIANT, bool SKIP>
 __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   // WPS = waves per SIMD the register budget is cut for: 2 keeps two sets of key fragments and r_j
   // (prefetch one subtile ahead), 3 keeps one set and relies on the other waves to hide LDS latency.
@@ -86,10 +92,13 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   static_assert(NW == 2 || NW == 4, "the DMA split assumes 2 or 4 waves");
   static_assert(RT >= 2, "the r_j prefetch needs at least two row tiles per wave");
   static_assert(LOADS % NW == 0, "tile rows must split evenly over the waves");
-  // LDS map: [pseudo-keys | tile 0 | tile 1 | r_j of tile 0 | r_j of tile 1]
+  // LDS map: [pseudo-keys | tile 0 | tile 1 | r_j of tile 0 | r_j of tile 1 | SKIP: counts, row records]
   constexpr int OFF_TILE = kPseudoBytes;
   constexpr int TILE_SPAN = LOADS * 1024;            // bytes the DMA copies of one tile cover
   constexpr int OFF_RJ = OFF_TILE + 2 * TILE_SPAN;
+  constexpr int OFF_CNT = OFF_RJ + 2 * TC * 4;       // two sets of NW open-row counts (by iteration parity)
+  constexpr int OFF_REC = OFF_CNT + 64;              // NW * 32 records of 5 words
+  static_assert(64 + NW * 32 * 20 <= kCompactBytes && 2 * NW * 4 <= 64, "record area");
 
   // Workgroups are dealt round-robin to the 8 XCDs; give every XCD whole heads so that a head's
   // keys are fetched into one L2 only.  A head's workgroups (row block x column part) are adjacent,
@@ -141,7 +150,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   const bool narrow = (KB == 2) && (n - rb * BM <= NW * 32);
   const int i0 = rb * BM + wave * (narrow ? 32 : RT * 32);
   const int tile_rows = narrow ? (1 << 20) : 32;     // row distance between a wave's row tiles
-  const bool active = i0 < n;                        // wave-uniform: does this wave own any candidate row?
+  bool active = i0 < n;                              // wave-uniform: does this wave own any candidate row?
   const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)gram_lds);   // LDS byte address of the dynamic segment
   const uint32_t row_bytes = (uint32_t)a.kst * 2u;
 
@@ -194,6 +203,11 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   bf16x8 res[RT][8];
   float thr[RT], sub[RT], rowdot[RT], rni[RT];
   int cnt[RT];
+  int rowid[RT];                                     // SKIP: the row a lane works for (-1: none); rows can move
+  auto row_of = [&](int rt) -> int {
+    if constexpr (SKIP) return rowid[rt];
+    else return i0 + rt * tile_rows + lrow;
+  };
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     const int rowc = min(i0 + rt * tile_rows + lrow, n - 1);
@@ -229,6 +243,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     sub[rt] = 0.f;
     cnt[rt] = 0;
     rowdot[rt] = 0.f;
+    rowid[rt] = row < n ? row : -1;
   }
   __syncthreads();
   if (t < kHeadDim) {
@@ -293,7 +308,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   };
   // Rare case: the row's hits in this tile, ranked by key (descending); forgive the first ones.
   auto tile_hits = [&](const f32x16& acc, const float (&rj)[16], int rt, int c0) {
-    const int row = i0 + rt * tile_rows + lrow;
+    const int row = row_of(rt);
     // Accumulator element i holds key c0 + 8*(i/4) + 4*half + i%4.  Masks are built with the bit
     // positions of half 0 (compile-time constants) and shifted by 4*half once.
     float tv[16];
@@ -361,11 +376,32 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     }
   };
 
-  // ---- stream the tiles, most recent first; RTE = row tiles of the wave that take part (RT, or 1 in a
-  // narrow row block)
-  auto scan = [&](auto rte) __attribute__((always_inline)) {
+  // Closed-form row sum minus the forgiven similarities of the row a lane holds in row tile rt
+  auto emit = [&](int rt) {
+    const int row = row_of(rt);
+    if ((unsigned)row < (unsigned)n) {
+      const float r = rn[row];
+      const float self = 1.0f - a.eps * r;               // r_i |K_i| = 1 - eps r_i
+      if (!split) {
+        const float total = r * rowdot[rt] - self * self - r * sub[rt];
+        a.sbar[(int64_t)head * a.n_pad + row] = total / (float)n;
+      } else {
+        // finalize subtracts the forgiven similarity once every part has reported its hit (beta = 1:
+        // the most recent part that found one supplies it)
+        a.part_cnt[((int64_t)head * parts + part) * a.n_pad + row] = cnt[rt];
+        a.part_pre[((int64_t)head * parts + part) * a.n_pad + row] = sub[rt];
+        if (closing) a.sbar[(int64_t)head * a.n_pad + row] = (r * rowdot[rt] - self * self) / (float)n;
+      }
+    }
+  };
+
+  // ---- stream the tiles, most recent first, from iteration it0 on; RTE = row tiles of the wave that take
+  // part (RT, or 1 in a narrow row block and after open rows have been gathered).  Returns the iteration
+  // to go on with in the one-row-tile form, or nct when the scan is over.
+  int tiles_now = narrow ? NW : NW * RT;               // SKIP: row tiles of the workgroup that may hold open rows
+  auto scan = [&](auto rte, int it0) __attribute__((always_inline)) -> int {
   constexpr int RTE = decltype(rte)::value;
-  for (int it = 0; it < nct; ++it) {
+  for (int it = it0; it < nct; ++it) {
     const int ct = ct_hi - 1 - it;
     const int buf = it & 1;
     // The next tile is copied while this one is used.  The last iteration copies its own tile once more
@@ -378,11 +414,13 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     // Optional exact shortcut: once every row of the wave has met beta hits nothing it could still
     // find changes its result, so the matrix work is skipped (the wave keeps copying tiles).
     bool live = active;
-    if (a.skip_saturated && live) {
-      bool open = false;
+    if constexpr (SKIP) {
+      if (live) {
+        bool open = false;
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) open = open || (thr[rt] != INFINITY);
-      live = __any(open);
+        for (int rt = 0; rt < RT; ++rt) open = open || (thr[rt] != INFINITY);
+        live = __any(open);
+      }
     }
     if (live) {
     bf16x8 kf[KB][8];
@@ -434,52 +472,95 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     }
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (a.skip_saturated) {
-      // leave the loop as soon as no wave of the workgroup has an open row (all copies have landed)
-      bool open = false;
-      if (active) {
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) open = open || (thr[rt] != INFINITY);
-      }
-      if (__syncthreads_or(open ? 1 : 0) == 0) break;
-    } else {
+    if constexpr (!SKIP) {
       __syncthreads();
+    } else {
+      // open rows of this wave, per row tile (one lane of each row's pair counts)
+      int mine = 0;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) mine += __popcll(__ballot(half == 0 && thr[rt] != INFINITY));
+      int* cbuf = reinterpret_cast<int*>(gram_lds + OFF_CNT) + (it & 1) * NW;
+      if (lane == 0) cbuf[wave] = mine;
+      __syncthreads();                                   // also publishes the next tile
+      int total = 0, before = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const int c = cbuf[w];
+        total += c;
+        before += (w < wave) ? c : 0;
+      }
+      if (total == 0) return nct;                        // nothing the remaining columns could change
+      const int need = (total + 31) >> 5;
+      if (need * 2 <= tiles_now && it + 1 < nct) {
+        // Gather the open rows: rows that are done are written out now, an open row's state goes to a
+        // record (slots in wave, row tile, lane order), and wave w takes records 32 w .. 32 w + 31 as its
+        // first row tile, fetching those rows' keys again.
+        float* rec = reinterpret_cast<float*>(gram_lds + OFF_REC);
+        int slot = before;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          const bool open = half == 0 && thr[rt] != INFINITY;
+          const unsigned long long ob = __ballot(open);
+          if (open) {
+            float* r5 = rec + 5 * (slot + __popcll(ob & ((1ull << lane) - 1ull)));
+            r5[0] = __int_as_float(rowid[rt]);
+            r5[1] = thr[rt];
+            r5[2] = sub[rt];
+            r5[3] = __int_as_float(cnt[rt]);
+            r5[4] = rowdot[rt];
+          } else if (half == 0) {
+            emit(rt);
+          }
+          slot += __popcll(ob);
+          rowid[rt] = -1;
+          thr[rt] = INFINITY;
+        }
+        __syncthreads();
+        const int sl = wave * 32 + lrow;
+        active = wave * 32 < total;
+        if (sl < total) {
+          const float* r5 = rec + 5 * sl;
+          rowid[0] = __float_as_int(r5[0]);
+          thr[0] = r5[1];
+          sub[0] = r5[2];
+          cnt[0] = __float_as_int(r5[3]);
+          rowdot[0] = r5[4];
+#pragma unroll
+          for (int kk = 0; kk < 8; ++kk) {
+            const uint4 x = *reinterpret_cast<const uint4*>(kbase + (int64_t)rowid[0] * a.kst + kk * 16 + half * 8);
+            __builtin_memcpy(&res[0][kk], &x, 16);
+          }
+        }
+        tiles_now = need;
+        if constexpr (RTE != 1) return it + 1;           // go on with one row tile per wave
+      }
     }
   }
+  return nct;
   };   // scan
-  if (narrow) scan(std::integral_constant<int, 1>{});
-  else scan(std::integral_constant<int, RT>{});
+  if constexpr (SKIP) {
+    int it = 0;
+    if (!narrow) it = scan(std::integral_constant<int, RT>{}, 0);
+    if (it < nct) scan(std::integral_constant<int, 1>{}, it);
+  } else {
+    if (narrow) scan(std::integral_constant<int, 1>{}, 0);
+    else scan(std::integral_constant<int, RT>{}, 0);
+  }
 
   // ---- closed-form row sums minus the forgiven similarities
   if (half == 0) {
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      const int row = i0 + rt * tile_rows + lrow;
-      if (row < n) {
-        const float r = rn[row];
-        const float self = 1.0f - a.eps * r;               // r_i |K_i| = 1 - eps r_i
-        if (!split) {
-          const float total = r * rowdot[rt] - self * self - r * sub[rt];
-          a.sbar[(int64_t)head * a.n_pad + row] = total / (float)n;
-        } else {
-          // finalize subtracts the forgiven similarity once every part has reported its hit (beta = 1:
-          // the most recent part that found one supplies it)
-          a.part_cnt[((int64_t)head * parts + part) * a.n_pad + row] = cnt[rt];
-          a.part_pre[((int64_t)head * parts + part) * a.n_pad + row] = sub[rt];
-          if (closing) a.sbar[(int64_t)head * a.n_pad + row] = (r * rowdot[rt] - self * self) / (float)n;
-        }
-      }
-    }
+    for (int rt = 0; rt < RT; ++rt) emit(rt);
   }
 }
 
-template <int NW, int RT, int TC, int WPS, int VARIANT>
+template <int NW, int RT, int TC, int WPS, int VARIANT, bool SKIP>
 hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   constexpr int BM = NW * RT * 32;
-  constexpr size_t lds = kPseudoBytes + 2 * (size_t)TC * kRowBytes + 2 * (size_t)TC * 4;
+  constexpr size_t lds = kPseudoBytes + 2 * (size_t)TC * kRowBytes + 2 * (size_t)TC * 4 + (SKIP ? kCompactBytes : 0);
   static bool configured = false;
   if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS, VARIANT>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
@@ -494,7 +575,7 @@ hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   const bool narrow_tail = a.row_blocks > 1 && pl.n - (a.row_blocks - 1) * BM <= NW * 32;
   a.tail_last = (narrow_tail && (int64_t)pl.heads * a.row_blocks <= 2048) ? 1 : 0;
   const dim3 grid((unsigned)((int64_t)head_groups * 8 * a.row_blocks * a.parts));
-  hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS, VARIANT>), grid, dim3(NW * 64), lds, stream, a);
+  hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP>), grid, dim3(NW * 64), lds, stream, a);
   return hipGetLastError();
 }
 
@@ -518,10 +599,14 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.row_blocks = 0; a.parts = pl.gram_parts;
   a.part_cnt = reinterpret_cast<int*>(ws + pl.off_pcnt);
   a.part_pre = reinterpret_cast<float*>(ws + pl.off_ppre);
-  a.skip_saturated = pl.skip_saturated ? 1 : 0;
-  if (a.credit != nullptr) return launch_shape<4, 2, 128, 2, kTransposed>(a, pl, stream);
-  if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit>(a, pl, stream);       // split only with beta = 1
-  return launch_shape<4, 2, 128, 2, kPlain>(a, pl, stream);
+  if (pl.skip_saturated) {
+    if (a.credit != nullptr) return launch_shape<4, 2, 128, 2, kTransposed, true>(a, pl, stream);
+    if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit, true>(a, pl, stream);
+    return launch_shape<4, 2, 128, 2, kPlain, true>(a, pl, stream);
+  }
+  if (a.credit != nullptr) return launch_shape<4, 2, 128, 2, kTransposed, false>(a, pl, stream);
+  if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit, false>(a, pl, stream);       // split only with beta = 1
+  return launch_shape<4, 2, 128, 2, kPlain, false>(a, pl, stream);
 }
 
 }  // namespace rkv

@@ -484,28 +484,66 @@ def test_empty_batch_is_a_no_op():
     assert st == rkv.RKV_OK and ko.shape == (0, 8, 1024, 128) and idx.shape == (0, 8, 1024)
 
 
-def test_skip_saturated_flag_gives_bit_identical_results():
-    """RKV_FLAG_SKIP_SATURATED only skips similarity tiles that cannot change a result."""
-    cases = [synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=4),
-             synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=2, sim_threshold=0.95, beta=2),
-             synth.scaled(synth.CONFIGS["cfg5_llama8b_b8192_bs4"], num_problems=1),
-             synth.CONFIGS["cfg1_tiny"]]
-    for w in cases:
-        P = w.num_problems
-        q, k, v = synth.make_batch(w)
-        qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
-        dense = shape_of(w, P)
-        skip = shape_of(w, P)
-        skip.flags = rkv.RKV_FLAG_SKIP_SATURATED
-        say(f"skip-saturated vs dense: {w.name} P={P} T={w.sim_threshold} beta={w.beta}")
-        a = rkv.rkv_compress(dense, qd, kd, vd, want_score=True)
-        b = rkv.rkv_compress(skip, qd, kd, vd, want_score=True)
-        ra, ma = rkv.rkv_score_redundancy(dense, kd, want_mean_sim=True)
-        rb, mb = rkv.rkv_score_redundancy(skip, kd, want_mean_sim=True)
-        torch.cuda.synchronize()
-        for x, y in zip(a[1:], b[1:]):
-            assert torch.equal(x, y)
-        assert torch.equal(ra, rb) and torch.equal(ma, mb)
+def _gradual(name, N, budget, P, H, beta, T, red, noise, seed):
+    """Gaussian keys, a fraction `red` of the rows noisy copies of earlier rows: a row meets its partners
+    anywhere in the scan, so the number of open rows falls gradually (several gathering stages)."""
+    return synth.Workload(name, P, H, 4 * H, N, budget, beta=beta, sim_threshold=T, seed=seed, recipe="rowcopy",
+                          redundancy=red, copy_noise=noise)
+
+
+SKIP_CASES = [
+    # workload, extra flags
+    (synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=4), 0),             # few heads: column scan split over workgroups
+    (synth.CONFIGS["cfg2_llama8b_b1024"], 0),                                            # full size: narrow last row blocks, listed last
+    (synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], beta=3), 0),
+    (synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=2, sim_threshold=0.95, beta=2), 0),
+    (synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=8), 32),            # other direction of the keep-recent rule
+    (synth.scaled(synth.CONFIGS["cfg3_llama8b_b4096"], num_problems=3), 0),
+    (synth.scaled(synth.CONFIGS["cfg5_llama8b_b8192_bs4"], num_problems=1), 0),
+    (synth.CONFIGS["cfg1_tiny"], 0),
+    (_gradual("gradual_b1", 1500, 1300, 40, 8, 1, 0.5, 0.9, 0.3, 501), 0),              # 1920 workgroups, six row blocks
+    (_gradual("gradual_b2", 1500, 1300, 2, 2, 2, 0.5, 0.95, 0.3, 502), 0),              # beta = 2: rows move with one partner met
+    (_gradual("gradual_narrow", 1400, 1200, 3, 2, 2, 0.5, 0.8, 0.3, 503), 0),           # last row block narrow (112 rows)
+    (_gradual("gradual_tr", 1400, 1200, 2, 2, 3, 0.5, 0.9, 0.3, 504), 32),
+    (_gradual("gradual_split", 2100, 1900, 1, 2, 1, 0.5, 0.9, 0.3, 505), 0),            # beta = 1, few heads: split scan
+    (_gradual("gradual_small", 300, 200, 2, 2, 2, 0.5, 0.7, 0.3, 506), 0),              # two row blocks, the second with 36 rows
+    (_gradual("none_similar", 1200, 1000, 2, 2, 1, 0.9, 0.0, 0.3, 507), 4),             # nothing is ever met: no row leaves
+]
+
+
+@pytest.mark.parametrize("w,flags", SKIP_CASES, ids=lambda x: x.name + f"_P{x.num_problems}_beta{x.beta}" if hasattr(x, "name") else f"flags{x}")
+def test_skip_saturated_flag_gives_bit_identical_results(w, flags):
+    """RKV_FLAG_SKIP_SATURATED only leaves out similarity tiles that cannot change a result, whatever
+    the order in which rows are done, moved to other waves or written out early."""
+    P = w.num_problems
+    q, k, v = synth.make_batch(w)
+    qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    dense = shape_of(w, P)
+    dense.flags = flags
+    skip = shape_of(w, P)
+    skip.flags = flags | rkv.RKV_FLAG_SKIP_SATURATED
+    say(f"skip-saturated vs dense: {w.name} P={P} H={w.kv_heads} N={w.n_tokens} T={w.sim_threshold} beta={w.beta} flags={flags}")
+    a = rkv.rkv_compress(dense, qd, kd, vd, want_score=True)
+    b = rkv.rkv_compress(skip, qd, kd, vd, want_score=True)
+    ra, ma = rkv.rkv_score_redundancy(dense, kd, want_mean_sim=True)
+    rb, mb = rkv.rkv_score_redundancy(skip, kd, want_mean_sim=True)
+    torch.cuda.synchronize()
+    assert torch.equal(ma, mb), f"mean similarity differs in {(ma != mb).sum().item()} entries"
+    assert torch.equal(ra, rb)
+    for x, y in zip(a[1:], b[1:]):
+        assert torch.equal(x, y)
+    if w.name.startswith("gradual"):
+        # the case does what it is for: some rows are done early, some late, some never
+        n = w.n_cand
+        kc = O.decode_bf16(k[0, 0][:n])
+        norm = np.sqrt((kc * kc).sum(1, keepdims=True)); kbar = kc / (norm + w.eps)
+        hits = (kbar @ kbar.T - np.eye(n)) > w.sim_threshold
+        done_at = np.full(n, -1)
+        for i in range(n):
+            cols = np.nonzero(hits[i])[0]
+            if len(cols) >= w.beta:
+                done_at[i] = cols[-w.beta]                      # the column at which row i has met beta partners
+        assert (done_at < 0).sum() >= 8 and (done_at >= n - 128).sum() >= 8 and ((done_at >= 0) & (done_at < n // 2)).sum() >= 8
 
 
 def test_largest_supported_cache_sampled_rows():
