@@ -80,7 +80,7 @@ enum GramVariant : int { kPlain = 0, kSplit = 1, kTransposed = 2 };
 
 constexpr int kCompactBytes = 3072;             // SKIP: open-row counts of the waves and the records of moved rows
 
-template <int NW, int RT, int TC, int WPS, int VARIANT, bool SKIP>
+template <int NW, int RT, int TC, int WPS, int VARIANT, bool SKIP, bool B1>
 __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   // WPS = waves per SIMD the register budget is cut for: 2 keeps two sets of key fragments and r_j
   // (prefetch one subtile ahead), 3 keeps one set and relies on the other waves to hide LDS latency.
@@ -366,6 +366,34 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
       if (cnt[rt] >= a.beta) thr[rt] = INFINITY;
     }
   };
+  // beta = 1 (B1): the row's most recent hit in this tile is all that is wanted.  Within a lane the
+  // accumulator elements are in ascending key order, so the last hit met wins; the two lanes of the row
+  // then compare keys.  DIAG: the tile holds the row's own key, which is no partner.
+  auto tile_first_hit = [&](const f32x16& acc, const float (&rj)[16], int rt, int c0, auto diag) {
+    const int selfl = row_of(rt) - c0 - 4 * half;            // own key in this lane's numbering, if it is here
+    float best = 0.f;
+    int bcol = -1;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float tvv = acc[i] * rj[i];
+      const int col = 8 * (i >> 2) + (i & 3);
+      bool hit = tvv > thr[rt];
+      if constexpr (decltype(diag)::value) hit = hit && (col != selfl);
+      best = hit ? tvv : best;
+      bcol = hit ? col : bcol;
+    }
+    const int mycol = bcol < 0 ? -1 : bcol + 4 * half;
+    const auto cols = __builtin_amdgcn_permlane32_swap((unsigned)mycol, (unsigned)mycol, false, false);
+    const auto vals = __builtin_amdgcn_permlane32_swap(__float_as_uint(best), __float_as_uint(best), false, false);
+    const bool low = (int)cols[0] > (int)cols[1];
+    const int col = low ? (int)cols[0] : (int)cols[1];
+    const float val = __uint_as_float(low ? vals[0] : vals[1]);
+    if (col >= 0) {
+      sub[rt] += val;
+      cnt[rt] = 1;
+      thr[rt] = INFINITY;
+    }
+  };
   // Scheduling hint for a block holding one 8-MFMA chain and one tile test (about 24 vector-ALU
   // instructions): issue as 8 x (1 MFMA, 3 VALU) so the test runs in the shadow of the matrix pipe.
   auto interleave = [&]() {
@@ -458,7 +486,15 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
         const int sp = NS - 1 - qp / RTE, rtp = qp % RTE;
         const float m = tile_max(acc[qp & 1], rj[sp % KB]);
         if (q2 < NS * RTE) interleave();
-        if (__any(m > thr[rtp])) tile_hits(acc[qp & 1], rj[sp % KB], rtp, ct * TC + sp * 32);
+        if (__any(m > thr[rtp])) {
+          if constexpr (B1) {
+            const int c0 = ct * TC + sp * 32;
+            if (c0 == i0 + rtp * 32) tile_first_hit(acc[qp & 1], rj[sp % KB], rtp, c0, std::true_type{});
+            else tile_first_hit(acc[qp & 1], rj[sp % KB], rtp, c0, std::false_type{});
+          } else {
+            tile_hits(acc[qp & 1], rj[sp % KB], rtp, ct * TC + sp * 32);
+          }
+        }
         if constexpr (KB == 2 && RTE == 1) {
           // subtile sp's test is done: its r_j registers take those of subtile sp - 2
           if (sp >= 2) read_rj(rj[sp & 1], rjs, sp - 2);
@@ -554,13 +590,13 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   }
 }
 
-template <int NW, int RT, int TC, int WPS, int VARIANT, bool SKIP>
+template <int NW, int RT, int TC, int WPS, int VARIANT, bool SKIP, bool B1 = false>
 hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   constexpr int BM = NW * RT * 32;
   constexpr size_t lds = kPseudoBytes + 2 * (size_t)TC * kRowBytes + 2 * (size_t)TC * 4 + (SKIP ? kCompactBytes : 0);
   static bool configured = false;
   if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP, B1>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
@@ -575,7 +611,7 @@ hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   const bool narrow_tail = a.row_blocks > 1 && pl.n - (a.row_blocks - 1) * BM <= NW * 32;
   a.tail_last = (narrow_tail && (int64_t)pl.heads * a.row_blocks <= 2048) ? 1 : 0;
   const dim3 grid((unsigned)((int64_t)head_groups * 8 * a.row_blocks * a.parts));
-  hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP>), grid, dim3(NW * 64), lds, stream, a);
+  hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP, B1>), grid, dim3(NW * 64), lds, stream, a);
   return hipGetLastError();
 }
 
@@ -606,6 +642,7 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   }
   if (a.credit != nullptr) return launch_shape<4, 2, 128, 2, kTransposed, false>(a, pl, stream);
   if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit, false>(a, pl, stream);       // split only with beta = 1
+  if (pl.beta == 1) return launch_shape<4, 2, 128, 2, kPlain, false, true>(a, pl, stream);
   return launch_shape<4, 2, 128, 2, kPlain, false>(a, pl, stream);
 }
 
