@@ -184,6 +184,9 @@ ADVERSARIAL = [
     (1100, 900, 1, 1, 64, 120, 1, 0.5, 0.1),   # alpha = 64 with 2W = 240: 56 columns per staging block, 19 blocks
     (900, 700, 1, 2, 8, 3, 1, 0.5, 0.1),       # W odd: the pooling window is not a multiple of four entries
     (5000, 4600, 2, 4, 8, 4, 1, 0.5, 0.1),     # two heads of 4992 candidates: one large staging block each
+    (600, 9, 2, 4, 8, 4, 1, 0.5, 0.1),         # a single candidate is kept (k = 1)
+    (600, 599, 2, 4, 8, 4, 1, 0.5, 0.1),       # a single candidate is evicted (k = n - 1)
+    (140, 139, 1, 2, 8, 2, 2, 0.5, 0.9),       # the same within one and a bit tiles
 ]
 
 
