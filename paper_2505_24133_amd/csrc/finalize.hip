@@ -51,16 +51,8 @@ struct FinArgs {
   float lambda;
 };
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
+__device__ __forceinline__ float wave_max(float v) { return full_wave_max(v); }
+__device__ __forceinline__ float wave_sum(float v) { return full_wave_sum(v); }
 // Workgroup reductions in a fixed order (deterministic); `buf` holds kFinWaves floats.
 __device__ float block_max(float v, float* buf) {
   v = wave_max(v);
@@ -83,12 +75,7 @@ __device__ float block_sum(float v, float* buf) {
 // Exclusive prefix sum of one uint per thread over the workgroup; also returns the total.
 __device__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* buf, uint32_t* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t inc = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t y = __shfl_up(inc, o);
-    if (lane >= o) inc += y;
-  }
+  const uint32_t inc = wave_inclusive_scan(v);
   __syncthreads();
   if (lane == 63) buf[wave] = inc;
   __syncthreads();
@@ -134,8 +121,8 @@ __device__ void select_and_emit(const uint32_t* keys, int n, int k_sel, int alph
       // scores of one head are often close: count the wave's most common digit with one atomic
       const unsigned long long am = __ballot(live);
       if (am != 0ull) {
-        const int first = __ffsll((long long)am) - 1;
-        const uint32_t d0 = __shfl(digit, first);
+        const int first = __builtin_amdgcn_readfirstlane(__ffsll((long long)am) - 1);
+        const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)digit, first);
         const unsigned long long same = __ballot(live && digit == d0);
         if (lane == first) atomicAdd(&h[d0], (uint32_t)__popcll(same));
         live = live && (digit != d0);
@@ -148,12 +135,7 @@ __device__ void select_and_emit(const uint32_t* keys, int n, int k_sel, int alph
       // the krem-th largest key is the one whose bins above it hold fewer than krem keys
       const uint32_t b0 = h[255 - 4 * lane], b1 = h[254 - 4 * lane], b2 = h[253 - 4 * lane], b3 = h[252 - 4 * lane];
       const uint32_t mine = (b0 + b1) + (b2 + b3);
-      uint32_t inc = mine;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t y = __shfl_up(inc, o);
-        if (lane >= o) inc += y;
-      }
+      const uint32_t inc = wave_inclusive_scan(mine);
       const uint32_t a0 = inc - mine, a1 = a0 + b0, a2 = a1 + b1, a3 = a2 + b2;
       uint32_t* s3 = sel + pass * 3;
       if (a0 < krem && a1 >= krem) { s3[0] = 255u - 4u * lane; s3[1] = a0; s3[2] = b0; }

@@ -19,35 +19,6 @@ constexpr int kLogitStride = kChunk + 8;   // floats; +8 puts the two half-waves
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
-// v + (v of the lane selected by the DPP control), within rows of 16 lanes.
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v) {
-  const int x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
-  return v + __int_as_float(x);
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_max(float v) {
-  const int x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
-  return fmaxf(v, __int_as_float(x));
-}
-// Reductions over the 32 lanes of each half of the wave (every lane of the half ends with the result):
-// four DPP steps inside the rows of 16 lanes, one row swap between the two rows.
-__device__ __forceinline__ float half_wave_max(float v) {
-  v = dpp_max<0xB1>(v);     // quad_perm [1,0,3,2]
-  v = dpp_max<0x4E>(v);     // quad_perm [2,3,0,1]
-  v = dpp_max<0x141>(v);    // row_half_mirror
-  v = dpp_max<0x140>(v);    // row_mirror
-  return pair_max16(v);
-}
-__device__ __forceinline__ float half_wave_sum(float v) {
-  v = dpp_add<0xB1>(v);
-  v = dpp_add<0x4E>(v);
-  v = dpp_add<0x141>(v);
-  v = dpp_add<0x140>(v);
-  return pair_sum16(v);
-}
-
 struct PrepassArgs {
   const uint16_t* q;      // [P, Hq, alpha, d] or nullptr
   const uint16_t* k;

@@ -130,5 +130,53 @@ __device__ __forceinline__ float pair_max16(float v) {
   const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
+__device__ __forceinline__ float pair_max32(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// v + (v of the lane selected by the DPP control), within rows of 16 lanes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return v + __int_as_float(x);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v) {
+  const int x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return fmaxf(v, __int_as_float(x));
+}
+// Reductions over the 32 lanes of each half of the wave (every lane of the half ends with the result):
+// four DPP steps inside the rows of 16 lanes, one row swap between the two rows.  The full-wave forms
+// add the swap between the halves.  All lanes must be active.
+__device__ __forceinline__ float half_wave_max(float v) {
+  v = dpp_max<0xB1>(v);     // quad_perm [1,0,3,2]
+  v = dpp_max<0x4E>(v);     // quad_perm [2,3,0,1]
+  v = dpp_max<0x141>(v);    // row_half_mirror
+  v = dpp_max<0x140>(v);    // row_mirror
+  return pair_max16(v);
+}
+__device__ __forceinline__ float half_wave_sum(float v) {
+  v = dpp_add<0xB1>(v);
+  v = dpp_add<0x4E>(v);
+  v = dpp_add<0x141>(v);
+  v = dpp_add<0x140>(v);
+  return pair_sum16(v);
+}
+__device__ __forceinline__ float full_wave_max(float v) { return pair_max32(half_wave_max(v)); }
+__device__ __forceinline__ float full_wave_sum(float v) { return pair_sum32(half_wave_sum(v)); }
+
+// Inclusive prefix sum over the 64 lanes: shifts by 1, 2, 4, 8 inside the rows of 16 lanes (a lane
+// without a source adds 0), then lane 15 of rows 0 and 2 is added to rows 1 and 3, and lane 31 to
+// rows 2 and 3.  All lanes must be active.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);   // row_shr:1
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);   // row_shr:2
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);   // row_shr:4
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);   // row_shr:8
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
+  return x;
+}
 
 }  // namespace rkv
