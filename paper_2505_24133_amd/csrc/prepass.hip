@@ -252,12 +252,9 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
     // ---- per-chunk softmax statistics for each written row
     for (int j = wave; j < a.out_rows; j += 4) {
       const float x0 = lg[j][lane], x1 = lg[j][lane + 64];
-      float m = fmaxf(x0, x1);
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-      float s = expf(x0 - m) + expf(x1 - m);     // exp(-inf) = 0 for masked keys; key j0 is always valid
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+      const float m = full_wave_max(fmaxf(x0, x1));
+      // exp(-inf) = 0 for masked keys; key j0 is always valid
+      const float s = full_wave_sum(expf(x0 - m) + expf(x1 - m));
       if (lane == 0) {
         float* st = a.stats + (((int64_t)head * a.chunks + chunk) * a.out_rows + j) * 2;
         st[0] = m;
