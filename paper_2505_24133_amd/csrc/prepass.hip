@@ -217,7 +217,7 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
 #pragma unroll
       for (int i = 0; i < AH; ++i) mx[i] = half_wave_max(valid ? m[i] : -INFINITY);
 #pragma unroll
-      for (int i = 0; i < AH; ++i) e[i] = half_wave_sum(valid ? expf(m[i] - mx[i]) : 0.f);
+      for (int i = 0; i < AH; ++i) e[i] = half_wave_sum(valid ? __expf(m[i] - mx[i]) : 0.f);
       if (lrow == 0) {
 #pragma unroll
         for (int i = 0; i < AH; ++i) {
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
       const float x0 = lg[j][lane], x1 = lg[j][lane + 64];
       const float m = full_wave_max(fmaxf(x0, x1));
       // exp(-inf) = 0 for masked keys; key j0 is always valid
-      const float s = full_wave_sum(expf(x0 - m) + expf(x1 - m));
+      const float s = full_wave_sum(__expf(x0 - m) + __expf(x1 - m));
       if (lane == 0) {
         float* st = a.stats + (((int64_t)head * a.chunks + chunk) * a.out_rows + j) * 2;
         st[0] = m;
