@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
       m = wave_max(m);
       float den = 0.f;
       for (int c = lane; c < a.stat_groups; c += 64)
-        den += st[(int64_t)c * a.rows * 2 + 1] * expf(st[(int64_t)c * a.rows * 2] - m);
+        den += st[(int64_t)c * a.rows * 2 + 1] * __expf(st[(int64_t)c * a.rows * 2] - m);
       den = wave_sum(den);
       if (lane == 0) {
         gmax[j] = m;
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
     for (int i = t; i < n; i += kFinThreads) m = fmaxf(m, sb[i]);
     smax = block_max(m, red);
     float s = 0.f;
-    for (int i = t; i < n; i += kFinThreads) s += expf(sb[i] - smax);
+    for (int i = t; i < n; i += kFinThreads) s += __expf(sb[i] - smax);
     sinv = 1.0f / block_sum(s, red);
   }
   __syncthreads();
