@@ -54,15 +54,6 @@ struct FinArgs {
 __device__ __forceinline__ float wave_max(float v) { return full_wave_max(v); }
 __device__ __forceinline__ float wave_sum(float v) { return full_wave_sum(v); }
 // Workgroup reductions in a fixed order (deterministic); `buf` holds kFinWaves floats.
-__device__ float block_max(float v, float* buf) {
-  v = wave_max(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float r = buf[0];
-  for (int w = 1; w < kFinWaves; ++w) r = fmaxf(r, buf[w]);
-  return r;
-}
 __device__ float block_sum(float v, float* buf) {
   v = wave_sum(v);
   __syncthreads();
@@ -215,7 +206,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
       }
     }
   }
-  float smax = 0.f, sinv = 0.f;
+  float sinv = 0.f;
   if constexpr ((MODE & kModeRedundancy) != 0) {
     if (a.parts > 1) {
       // beta = 1 (the only case that is split): the most recent column part that found a hit supplies
@@ -240,11 +231,10 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
       const float unit = 9.094947017729282e-13f / (float)n;          // 2^-40 / n
       for (int i = t; i < n; i += kFinThreads) sb[i] -= (float)cr[i] * unit;
     }
-    float m = -INFINITY;
-    for (int i = t; i < n; i += kFinThreads) m = fmaxf(m, sb[i]);
-    smax = block_max(m, red);
+    // Eq. 6 as it stands: a mean of cosines lies in [-1, 1] (down to -2 with the partner counters taken
+    // off), so the exponentials need no shift by the maximum
     float s = 0.f;
-    for (int i = t; i < n; i += kFinThreads) s += __expf(sb[i] - smax);
+    for (int i = t; i < n; i += kFinThreads) s += __expf(sb[i]);
     sinv = 1.0f / block_sum(s, red);
   }
   __syncthreads();
@@ -416,7 +406,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
     }
     if constexpr ((MODE & kModeRedundancy) != 0) {
       const float s = sb[i];
-      rd = __expf(s - smax) * sinv;
+      rd = __expf(s) * sinv;
       if (a.red_out) a.red_out[(int64_t)head * n + i] = rd;
       if (a.sbar_out) a.sbar_out[(int64_t)head * n + i] = s;
     } else if constexpr ((MODE & kModeZ) != 0) {
