@@ -17,6 +17,8 @@ namespace rkv {
 
 namespace {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a type the non-temporal builtins accept
+
 constexpr int kIpThreads = 1024;
 constexpr int kIpDepth = 4;          // rows per thread and tile
 
@@ -93,7 +95,8 @@ __global__ __launch_bounds__(kIpThreads) void compact_inplace_kernel(InplaceArgs
 #pragma unroll
     for (int u = 0; u < kIpDepth; ++u) {
       const int r = r0 + u * rows_per_pass + slot;
-      if (r < a.budget) *reinterpret_cast<uint4*>(base + lay.offset(p, h, r)) = cur[u];
+      if (r < a.budget)      // non-temporal, as in the out-of-place gather: the moved rows are not read again here
+        __builtin_nontemporal_store(u32x4{cur[u].x, cur[u].y, cur[u].z, cur[u].w}, reinterpret_cast<u32x4*>(base + lay.offset(p, h, r)));
     }
     if (more) {
 #pragma unroll
