@@ -408,7 +408,9 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   auto emit = [&](int rt) {
     const int row = row_of(rt);
     if ((unsigned)row < (unsigned)n) {
-      const float r = rn[row];
+      float r;
+      if constexpr (SKIP) r = rn[row];                   // rows may have moved between lanes
+      else r = rni[rt];                                  // still in the register it was loaded into
       const float self = 1.0f - a.eps * r;               // r_i |K_i| = 1 - eps r_i
       if (!split) {
         const float total = r * rowdot[rt] - self * self - r * sub[rt];
