@@ -217,7 +217,7 @@ rkv_status rkv_compact_inplace(const rkv_params* prm, void* k, void* v, const in
   return hip_status(launch_compact_inplace(pl, k, v, kept_idx, static_cast<hipStream_t>(stream)));
 }
 
-// k_out == nullptr selects the in-place compaction of k and v.
+// `inplace` compacts inside k and v (k_out and v_out are then unused).
 static rkv_status compress_impl(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
                                 void* k_out, void* v_out, int32_t* kept_idx, float* score,
                                 void* ws, size_t ws_bytes, void* stream, void* const* events, bool inplace = false) {

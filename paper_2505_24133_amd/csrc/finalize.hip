@@ -447,13 +447,10 @@ __global__ __launch_bounds__(kFinThreads) void shared_select_kernel(const float*
 
 template <int MODE>
 hipError_t launch_mode(const FinArgs& a, int heads, size_t lds, hipStream_t stream) {
-  static bool configured = false;
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&finalize_kernel<MODE>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  // once per kernel instantiation (initialisation of a function-local static is thread-safe)
+  static const hipError_t configured = hipFuncSetAttribute(reinterpret_cast<const void*>(&finalize_kernel<MODE>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+  if (configured != hipSuccess) return configured;
   hipLaunchKernelGGL((finalize_kernel<MODE>), dim3(heads), dim3(kFinThreads), lds, stream, a);
   return hipGetLastError();
 }
@@ -518,13 +515,9 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
 }
 
 hipError_t launch_shared_select(const Plan& pl, char* ws, int32_t* kept_idx, hipStream_t stream) {
-  static bool configured = false;
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shared_select_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static const hipError_t configured = hipFuncSetAttribute(reinterpret_cast<const void*>(&shared_select_kernel),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
+  if (configured != hipSuccess) return configured;
   hipLaunchKernelGGL(shared_select_kernel, dim3(pl.P), dim3(kFinThreads), (size_t)pl.n_pad * sizeof(uint32_t), stream,
                      reinterpret_cast<const float*>(ws + pl.off_z), kept_idx, pl.H, pl.n, pl.n_pad, pl.k_sel,
                      pl.alpha, pl.budget);

@@ -596,13 +596,11 @@ template <int NW, int RT, int TC, int WPS, int VARIANT, bool SKIP, bool B1 = fal
 hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
   constexpr int BM = NW * RT * 32;
   constexpr size_t lds = kPseudoBytes + 2 * (size_t)TC * kRowBytes + 2 * (size_t)TC * 4 + (SKIP ? kCompactBytes : 0);
-  static bool configured = false;
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP, B1>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  // once per kernel instantiation (initialisation of a function-local static is thread-safe)
+  static const hipError_t configured =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP, B1>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (configured != hipSuccess) return configured;
   static_assert(BM == kGramRows && TC == kGramTile, "the plan's split of the similarity pass assumes this shape");
   const int head_groups = (pl.heads + 7) / 8;
   a.row_blocks = (pl.n + BM - 1) / BM;
