@@ -61,9 +61,7 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
   // Persistent workgroups: each walks over (head, chunk) items.  Four workgroups share a compute unit
   // (128 VGPRs, 37 KB of LDS each), so while one waits for its chunk the others compute; holding the
   // next chunk in registers as well cost a workgroup per compute unit and was slower.
-  auto fetch = [&](int item, uint4 (&dst)[8]) {
-    const int hd = item / a.chunks;
-    const int ck = item - hd * a.chunks;
+  auto fetch = [&](int hd, int ck, uint4 (&dst)[8]) {
     const int pp = hd / a.H;
     // rows past n repeat row n - 1 (their r is forced to 0 below and their logits are masked)
     if constexpr (PAGED) {
@@ -87,13 +85,19 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
   };
   uint4 regs[8];
 
-  for (int item = blockIdx.x; item < a.items; item += gridDim.x) {
-  const int head = item / a.chunks;
-  const int chunk = item - head * a.chunks;
+  // Walk order (the grid is a multiple of 8 workgroups, dealt round-robin to the 8 XCDs): the workgroups
+  // of XCD x take the heads with head % 8 == x, which is where the similarity pass will read their keys
+  // again, and take them last head first, so that what this kernel leaves in an XCD's L2 are the heads
+  // the similarity pass starts with.
+  const int xcd = blockIdx.x & 7;
+  const int heads_x = (a.items / a.chunks - xcd + 7) >> 3;
+  for (int li = blockIdx.x >> 3; li < heads_x * a.chunks; li += gridDim.x >> 3) {
+  const int head = (heads_x - 1 - li / a.chunks) * 8 + xcd;
+  const int chunk = li % a.chunks;
   const int p = head / a.H;
   const int h = head - p * a.H;
   const int j0 = chunk * kChunk;
-  fetch(item, regs);
+  fetch(head, chunk, regs);
   // the query fragments of this head are requested now and used after the norms: their latency hides
   // behind the first stage (rows past G * alpha repeat the last one; their results are not read)
   bf16x8 qf[MT][8];
@@ -278,7 +282,9 @@ void launch_paged(const PrepassArgs& a, hipStream_t stream) {
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
     return per_cu * cus;
   }();
-  const dim3 grid((unsigned)std::min(a.items, res)), block(kPrepassThreads);
+  // a multiple of 8 workgroups, at most one per item of the XCD with the most heads
+  const int per_xcd = std::max(1, std::min(((a.items / a.chunks + 7) / 8) * a.chunks, res / 8));
+  const dim3 grid((unsigned)(8 * per_xcd)), block(kPrepassThreads);
   hipLaunchKernelGGL((prepass_kernel<HAS_Q, MT, AH, PAGED>), grid, block, 0, stream, a);
 }
 
