@@ -901,3 +901,30 @@ def test_shared_workspace_across_shapes():
         torch.cuda.synchronize()
         for x, y in zip(outs[w.name][1:], o[1:]):
             assert torch.equal(x, y)
+
+
+def test_bench_prints_one_json_line_with_the_agreed_fields(repo_root):
+    """bench.py on the GPU, a few steps: one JSON line with the throughput, the dominant kernel's
+    roofline entry and the CPU oracle's rate."""
+    import json
+    import subprocess
+    import sys
+    say("bench.py --steps 3 (child process)")
+    r = subprocess.run([sys.executable, "bench.py", "--steps", "3", "--warmup", "1", "--no-other-modes", "--cpu-seconds", "1"],
+                       cwd=repo_root, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["warmup"] == 1 and d["higher_is_better"] is True
+    assert d["config"]["workload"] == "cfg2_llama8b_b1024" and d["data"] == "synthetic" and d["vs_baseline"] is None
+    assert d["value"] > 0 and abs(d["value"] * d["ms_per_step"] - 1000.0) < 1.0
+    roof = d["roofline"]
+    assert roof["bound"] == "mfma" and roof["unit"] == "TFLOP/s" and roof["peak"] == 2500.0
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9 and 0.05 < roof["frac"] < 1.0
+    assert roof["traffic"] is None or roof["traffic"] > 0
+    cpu = d["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["unit"] == d["unit"] and cpu["sample"]
