@@ -170,7 +170,9 @@ __device__ void select_and_emit(const uint32_t* keys, int n, int k_sel, int alph
 
 constexpr int kModeZ = kModeSelect | kModeScore;     // modes that form the joint score
 
-template <int MODE>
+// PLAIN != 0: the default readings with a window that is a multiple of four wide and an unsplit
+// similarity pass; the variants' branches are then compiled out of the instantiation.
+template <int MODE, int PLAIN>
 __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t keys[];   // n_pad order-preserving keys (select mode) / pooling stage
   __shared__ float red[kFinWaves];
@@ -183,22 +185,31 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   const int lane = t & 63;
   const int head = blockIdx.x;
   const int n = a.n;
-  const float* lg = a.logit + (int64_t)head * a.rows * a.n_pad;
+  // PLAIN == 2 additionally fixes the paper's window sizes, alpha = 8 and W = 4, at compile time
+  const int alpha = (PLAIN == 2) ? 8 : a.alpha;
+  const int W = (PLAIN == 2) ? 4 : a.W;
+  const int qrows = PLAIN ? alpha : a.rows;
+  const int pool_rows = PLAIN ? alpha : a.pool_rows;
+  const int group_mode = PLAIN ? 0 : a.group_mode;
+  const bool pool_after_mean = PLAIN ? false : a.pool_after_mean != 0;
+  const int sim_parts = PLAIN ? 1 : a.parts;
+  const unsigned long long* credit = PLAIN ? nullptr : a.credit;
+  const float* lg = a.logit + (int64_t)head * qrows * a.n_pad;
   float* sb = a.sbar + (int64_t)head * a.n_pad;
 
   // ---- softmax denominators: one wave per query row, lanes over the chunks
   if constexpr ((MODE & kModeImportance) != 0) {
     // the factor 1 / alpha of the mean over the query rows (and 1 / G of the mean over the group's
     // heads, when that is how they are merged) is folded into the softmax normaliser
-    const float parts = (float)a.alpha * (a.group_mode == 2 ? (float)a.G : 1.0f);
-    for (int j = t >> 6; j < a.rows; j += kFinWaves) {
-      const float* st = a.stats + ((int64_t)head * a.stat_groups * a.rows + j) * 2;
+    const float parts = (float)alpha * (group_mode == 2 ? (float)a.G : 1.0f);
+    for (int j = t >> 6; j < qrows; j += kFinWaves) {
+      const float* st = a.stats + ((int64_t)head * a.stat_groups * qrows + j) * 2;
       float m = -INFINITY;
-      for (int c = lane; c < a.stat_groups; c += 64) m = fmaxf(m, st[(int64_t)c * a.rows * 2]);
+      for (int c = lane; c < a.stat_groups; c += 64) m = fmaxf(m, st[(int64_t)c * qrows * 2]);
       m = wave_max(m);
       float den = 0.f;
       for (int c = lane; c < a.stat_groups; c += 64)
-        den += st[(int64_t)c * a.rows * 2 + 1] * __expf(st[(int64_t)c * a.rows * 2] - m);
+        den += st[(int64_t)c * qrows * 2 + 1] * __expf(st[(int64_t)c * qrows * 2] - m);
       den = wave_sum(den);
       if (lane == 0) {
         gmax[j] = m;
@@ -208,14 +219,14 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   }
   float sinv = 0.f;
   if constexpr ((MODE & kModeRedundancy) != 0) {
-    if (a.parts > 1) {
+    if (sim_parts > 1) {
       // beta = 1 (the only case that is split): the most recent column part that found a hit supplies
       // the forgiven similarity
       const float inv_n = 1.0f / (float)n;
       for (int i = t; i < n; i += kFinThreads) {
         float forgiven = 0.f;
-        for (int p = a.parts - 1; p >= 0; --p) {
-          const int64_t at = ((int64_t)head * a.parts + p) * a.n_pad + i;
+        for (int p = sim_parts - 1; p >= 0; --p) {
+          const int64_t at = ((int64_t)head * sim_parts + p) * a.n_pad + i;
           if (a.part_cnt[at] > 0) {
             forgiven = a.part_pre[at];
             break;
@@ -224,10 +235,10 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
         sb[i] -= a.rnorm[(int64_t)head * a.n_pad + i] * forgiven * inv_n;
       }
     }
-    if (a.credit != nullptr) {
+    if (credit != nullptr) {
       // transposed recency rule: the similarity pass charged the forgiven entries to the recent
       // partner; every thread rewrites the elements it reads again below
-      const unsigned long long* cr = a.credit + (int64_t)head * a.n_pad;
+      const unsigned long long* cr = credit + (int64_t)head * a.n_pad;
       const float unit = 9.094947017729282e-13f / (float)n;          // 2^-40 / n
       for (int i = t; i < n; i += kFinThreads) sb[i] -= (float)cr[i] * unit;
     }
@@ -245,40 +256,40 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   if constexpr ((MODE & kModeImportance) != 0) {
     imp_dst = a.imp_out ? a.imp_out + (int64_t)head * n : a.imp_tmp + (int64_t)head * a.n_pad;
     float* pool = reinterpret_cast<float*>(keys);            // the key buffer is not in use yet
-    const int win = (a.W > 0) ? 2 * a.W : 1;
+    const int win = (W > 0) ? 2 * W : 1;
     const int halo = win - 1;
     // columns per staging block: a multiple of four, leaving room for the window behind the last one
-    const int block_cols = (a.pool_floats / a.pool_rows - win) & ~3;   // >= 4 (checked on the host)
+    const int block_cols = (a.pool_floats / pool_rows - win) & ~3;   // >= 4 (checked on the host)
     // W even: four neighbouring candidates share all but three entries of their windows, so one thread
     // serves four candidates from 16-byte LDS reads
-    const bool strips = win >= 4 && (win & 3) == 0;
+    const bool strips = PLAIN || (win >= 4 && (win & 3) == 0);
     for (int cb = 0; cb < n; cb += block_cols) {
       const int cols = min(block_cols, n - cb);
       const int width = cols + halo;
       const int stride = ((cols + 3) & ~3) + win;              // floats per staged row, a multiple of four if `strips`
-      const int first = cb - a.W;                              // column held at pool[j][0]
-      if (a.group_mode != 0) {
+      const int first = cb - W;                              // column held at pool[j][0]
+      if (group_mode != 0) {
         // App. A.2 variants: the attention scores of every query head first (softmax per head), then
         // the max or the mean over the G heads of the group; the staging buffer holds these scores
         // (0 outside [0, n), which never wins a max over scores >= 0)
-        for (int j = 0; j < a.alpha; ++j)
+        for (int j = 0; j < alpha; ++j)
           for (int c = t; c < width; c += kFinThreads) {
             const int col = first + c;
             float pr = 0.f;
             if (col >= 0 && col < n)
               for (int g = 0; g < a.G; ++g) {
-                const int row = g * a.alpha + j;
+                const int row = g * alpha + j;
                 const float x = __expf(lg[(int64_t)row * a.n_pad + col] - gmax[row]) * ginv[row];
-                pr = (a.group_mode == 1) ? fmaxf(pr, x) : pr + x;
+                pr = (group_mode == 1) ? fmaxf(pr, x) : pr + x;
               }
             pool[j * width + c] = pr;
           }
         __syncthreads();
-        if (a.pool_after_mean) {
-          float* avg = pool + a.alpha * width;
+        if (pool_after_mean) {
+          float* avg = pool + alpha * width;
           for (int c = t; c < width; c += kFinThreads) {
             float s = 0.f;
-            for (int j = 0; j < a.alpha; ++j) s += pool[j * width + c];
+            for (int j = 0; j < alpha; ++j) s += pool[j * width + c];
             avg[c] = s;
           }
           __syncthreads();
@@ -290,7 +301,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
         } else {
           for (int li = t; li < cols; li += kFinThreads) {
             float imp = 0.f;
-            for (int j = 0; j < a.alpha; ++j) {
+            for (int j = 0; j < alpha; ++j) {
               float m = pool[j * width + li];
               for (int c = 1; c < win; ++c) m = fmaxf(m, pool[j * width + li + c]);
               imp += m;
@@ -304,7 +315,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
       // eight query rows x two column slots: sixteen independent loads per thread are in flight
       // before the first LDS store
       for (int c0 = 0; c0 < stride; c0 += 2 * kFinThreads)
-      for (int j0 = 0; j0 < a.alpha; j0 += 8) {
+      for (int j0 = 0; j0 < alpha; j0 += 8) {
         float v[8][2];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
@@ -312,7 +323,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
           for (int sl = 0; sl < 2; ++sl) {
             const int c = c0 + t + sl * kFinThreads;
             const int col = first + c;
-            v[u][sl] = (j0 + u < a.alpha && c < width && col >= 0 && col < n)
+            v[u][sl] = (j0 + u < alpha && c < width && col >= 0 && col < n)
                            ? lg[(int64_t)(j0 + u) * a.n_pad + col] : -INFINITY;      // -inf also fills width .. stride - 1
           }
 #pragma unroll
@@ -320,18 +331,18 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
 #pragma unroll
           for (int sl = 0; sl < 2; ++sl) {
             const int c = c0 + t + sl * kFinThreads;
-            if (j0 + u < a.alpha && c < stride) pool[(j0 + u) * stride + c] = v[u][sl];
+            if (j0 + u < alpha && c < stride) pool[(j0 + u) * stride + c] = v[u][sl];
           }
       }
       __syncthreads();
-      if (a.pool_after_mean) {
+      if (pool_after_mean) {
         // Alg. 1 order: the mean over the query rows of the attention weights first (one extra LDS
         // row; columns outside [0, n) hold exp(-inf) = 0, which never wins a max over weights >= 0
         // because every window holds its own column), then the sliding max of that row
-        float* avg = pool + a.alpha * stride;
+        float* avg = pool + alpha * stride;
         for (int c = t; c < width; c += kFinThreads) {
           float s = 0.f;
-          for (int j = 0; j < a.alpha; ++j) s += __expf(pool[j * stride + c] - gmax[j]) * ginv[j];
+          for (int j = 0; j < alpha; ++j) s += __expf(pool[j * stride + c] - gmax[j]) * ginv[j];
           avg[c] = s;
         }
         __syncthreads();
@@ -348,7 +359,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
         for (int g = t; 4 * g < cols; g += kFinThreads) {
           float imp[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
-          for (int j = 0; j < a.alpha; ++j) {
+          for (int j = 0; j < alpha; ++j) {
             // candidates 4g .. 4g+3 of this block: windows [4g + k, 4g + k + win - 1] in staged numbering
             const float4* rowp = reinterpret_cast<const float4*>(pool + j * stride + 4 * g);
             const float4 head4 = rowp[0];
@@ -378,18 +389,18 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
       for (int li = t; li < cols; li += kFinThreads) {
         float imp = 0.f;
         // eight query rows at a time: their window reads are independent LDS loads
-        for (int j0 = 0; j0 < a.alpha; j0 += 8) {
+        for (int j0 = 0; j0 < alpha; j0 += 8) {
           float m[8];
 #pragma unroll
           for (int u = 0; u < 8; ++u) m[u] = -INFINITY;
           for (int c = 0; c < win; ++c) {
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-              if (j0 + u < a.alpha) m[u] = fmaxf(m[u], pool[(j0 + u) * stride + li + c]);   // window [i - W, i + W - 1]
+              if (j0 + u < alpha) m[u] = fmaxf(m[u], pool[(j0 + u) * stride + li + c]);   // window [i - W, i + W - 1]
           }
 #pragma unroll
           for (int u = 0; u < 8; ++u)
-            if (j0 + u < a.alpha) imp += __expf(m[u] - gmax[j0 + u]) * ginv[j0 + u];
+            if (j0 + u < alpha) imp += __expf(m[u] - gmax[j0 + u]) * ginv[j0 + u];
         }
         imp_dst[cb + li] = imp;
       }
@@ -422,7 +433,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
 
   if constexpr ((MODE & kModeSelect) != 0) {
     __syncthreads();
-    select_and_emit(keys, n, a.k_sel, a.alpha, a.kept + (int64_t)head * a.budget, 1, 0, hist, scan_buf, sel);
+    select_and_emit(keys, n, a.k_sel, alpha, a.kept + (int64_t)head * a.budget, 1, 0, hist, scan_buf, sel);
   }
 }
 
@@ -445,14 +456,19 @@ __global__ __launch_bounds__(kFinThreads) void shared_select_kernel(const float*
   select_and_emit(keys, n, k_sel, alpha, kept + (int64_t)p * H * budget, H, budget, hist, scan_buf, sel);
 }
 
-template <int MODE>
-hipError_t launch_mode(const FinArgs& a, int heads, size_t lds, hipStream_t stream) {
+template <int MODE, int PLAIN>
+hipError_t launch_plain(const FinArgs& a, int heads, size_t lds, hipStream_t stream) {
   // once per kernel instantiation (initialisation of a function-local static is thread-safe)
-  static const hipError_t configured = hipFuncSetAttribute(reinterpret_cast<const void*>(&finalize_kernel<MODE>),
+  static const hipError_t configured = hipFuncSetAttribute(reinterpret_cast<const void*>(&finalize_kernel<MODE, PLAIN>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, 32768 * 4);
   if (configured != hipSuccess) return configured;
-  hipLaunchKernelGGL((finalize_kernel<MODE>), dim3(heads), dim3(kFinThreads), lds, stream, a);
+  hipLaunchKernelGGL((finalize_kernel<MODE, PLAIN>), dim3(heads), dim3(kFinThreads), lds, stream, a);
   return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t launch_mode(const FinArgs& a, int heads, size_t lds, hipStream_t stream) {
+  return launch_plain<MODE, 0>(a, heads, lds, stream);
 }
 
 }  // namespace
@@ -497,6 +513,15 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
     words = std::max(words, pool);
   }
   const size_t lds = words * sizeof(uint32_t);
+  // the instantiation without the variants' branches serves the default readings with W a positive
+  // multiple of four (other shapes and flags take the general one; only the fused modes are doubled)
+  const bool plain = pl.gqa_mode == 0 && !pl.pool_after_mean && pl.gram_parts == 1 && !pl.recency_transposed &&
+                     pl.W > 0 && (pl.W & 1) == 0;
+  if (plain && mode == (kModeImportance | kModeRedundancy | kModeSelect)) {
+    if (pl.alpha == 8 && pl.W == 4)
+      return launch_plain<kModeImportance | kModeRedundancy | kModeSelect, 2>(a, pl.heads, lds, stream);
+    return launch_plain<kModeImportance | kModeRedundancy | kModeSelect, 1>(a, pl.heads, lds, stream);
+  }
   switch (mode) {
     case kModeImportance: return launch_mode<kModeImportance>(a, pl.heads, lds, stream);
     case kModeRedundancy: return launch_mode<kModeRedundancy>(a, pl.heads, lds, stream);
