@@ -27,7 +27,7 @@ HBM_PEAK = 8.0e12            # B/s
 # HBM bytes per launch of the similarity (Gram) kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this same command, scaled by a plain 256 MiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 KiB);
 # the runs are summarised in profiles/rkv_compress_cfg2_counters.md.
-GRAM_TRAFFIC_BYTES = {"cfg2_llama8b_b1024": int((9.054e4 * 2.0 + 1144) * 1024)}
+GRAM_TRAFFIC_BYTES = {"cfg2_llama8b_b1024": int((9.082e4 * 2.0 + 1144) * 1024)}
 
 
 def hip_runtime(torch):

@@ -513,15 +513,17 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
     words = std::max(words, pool);
   }
   const size_t lds = words * sizeof(uint32_t);
-  // the instantiation without the variants' branches serves the default readings with W a positive
-  // multiple of four (other shapes and flags take the general one; only the fused modes are doubled)
-  const bool plain = pl.gqa_mode == 0 && !pl.pool_after_mean && pl.gram_parts == 1 && !pl.recency_transposed &&
-                     pl.W > 0 && (pl.W & 1) == 0;
-  if (plain && mode == (kModeImportance | kModeRedundancy | kModeSelect)) {
-    if (pl.alpha == 8 && pl.W == 4)
-      return launch_plain<kModeImportance | kModeRedundancy | kModeSelect, 2>(a, pl.heads, lds, stream);
+  // the instantiations without the variants' branches serve the default readings with W a positive
+  // multiple of two (other shapes and flags take the general one; only the fused modes are doubled)
+  const bool plain_imp = pl.gqa_mode == 0 && !pl.pool_after_mean && pl.W > 0 && (pl.W & 1) == 0;
+  const bool plain_red = pl.gram_parts == 1 && !pl.recency_transposed;
+  const bool paper_window = pl.alpha == 8 && pl.W == 4;
+  if (plain_imp && plain_red && mode == (kModeImportance | kModeRedundancy | kModeSelect)) {
+    if (paper_window) return launch_plain<kModeImportance | kModeRedundancy | kModeSelect, 2>(a, pl.heads, lds, stream);
     return launch_plain<kModeImportance | kModeRedundancy | kModeSelect, 1>(a, pl.heads, lds, stream);
   }
+  if (plain_imp && paper_window && mode == (kModeImportance | kModeSelect))       // attention-only eviction
+    return launch_plain<kModeImportance | kModeSelect, 2>(a, pl.heads, lds, stream);
   switch (mode) {
     case kModeImportance: return launch_mode<kModeImportance>(a, pl.heads, lds, stream);
     case kModeRedundancy: return launch_mode<kModeRedundancy>(a, pl.heads, lds, stream);
