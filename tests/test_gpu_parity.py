@@ -940,3 +940,51 @@ def test_bench_prints_one_json_line_with_the_agreed_fields(repo_root):
     assert roof["traffic"] is None or roof["traffic"] > 0
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["unit"] == d["unit"] and cpu["sample"]
+
+
+def _random_case(seed):
+    """A supported shape drawn at random (seeded): odd group sizes and windows, beta beyond the number of
+    hits, thresholds at both ends, budgets from k = 1 to k = n - 1."""
+    rng = np.random.default_rng(1000 + seed)
+    alpha = int(rng.choice([1, 2, 3, 5, 8, 8, 8, 9, 12, 16, 16, 24, 32, 40, 64]))
+    G = int(rng.integers(1, 64 // alpha + 1))
+    G = min(G, 8)
+    H = int(rng.integers(1, 4))
+    n = int(rng.integers(alpha + 2, 1500))
+    N = n + alpha
+    budget = int(rng.integers(alpha + 1, N))
+    W = int(rng.choice([0, 1, 2, 3, 4, 4, 5, 8, 16, 33]))
+    while W > 0 and (alpha + 1) * 2 * W > 16384:
+        W //= 2
+    beta = int(rng.choice([0, 1, 1, 1, 2, 3, 7]))
+    T = float(rng.choice([0.0, 0.3, 0.5, 0.5, 0.8, 0.95, 1.0]))
+    lam = float(rng.choice([0.0, 0.05, 0.1, 0.1, 0.5, 0.9]))
+    recipe = str(rng.choice(["rowcopy", "spans", "clusters"]))
+    red = float(rng.uniform(0.1, 0.7))
+    return synth.Workload(f"rnd{seed}", 2, H, H * G, N, budget, alpha=alpha, pool_w=W, beta=beta, sim_threshold=T,
+                          lam=lam, seed=5000 + seed, recipe=recipe, redundancy=red, copy_noise=0.1,
+                          outlier_channels=int(rng.choice([0, 4])), n_clusters=int(rng.choice([4, 16, 64])))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_supported_shapes(seed):
+    w = _random_case(seed)
+    q, k, v = synth.make_batch(w)
+    run_fused(w, q, k, v, [(p, h) for p in range(2) for h in range(w.kv_heads)], w.name, check_parts=True)
+
+
+@pytest.mark.parametrize("seed", range(100, 116))
+def test_random_supported_shapes_with_variant_flags(seed):
+    """The same with a random combination of the variant flags (pooling order, shared selection, either
+    App. A.2 group merge, the other direction of the keep-recent rule, the exact shortcut)."""
+    w = _random_case(seed)
+    rng = np.random.default_rng(9000 + seed)
+    flags = int(rng.choice([0, rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MAX, rkv.RKV_FLAG_GQA_SOFTMAX_THEN_MEAN]))
+    for bit in (rkv.RKV_FLAG_SKIP_SATURATED, rkv.RKV_FLAG_POOL_AFTER_MEAN, rkv.RKV_FLAG_SHARED_SELECTION,
+                rkv.RKV_FLAG_RECENCY_TRANSPOSED):
+        if rng.random() < 0.5:
+            flags |= bit
+    if (flags & rkv.RKV_FLAG_POOL_AFTER_MEAN) and w.pool_w > 0 and (w.alpha + 1) * 2 * w.pool_w > 16384:
+        flags &= ~rkv.RKV_FLAG_POOL_AFTER_MEAN
+    q, k, v = synth.make_batch(w)
+    run_fused(w, q, k, v, [(p, h) for p in range(2) for h in range(w.kv_heads)], f"{w.name}_flags{flags}", flags=flags)
