@@ -11,7 +11,8 @@
  *     allocates, frees or keeps them.  `rkv_params` and `size_t*` are HOST pointers.
  *   - bf16 tensors are row-major with the head dimension innermost and contiguous:
  *       q_obs [P, q_heads, alpha, d]   observation queries; query head hq serves KV head
- *                                      hq / G, G = q_heads / kv_heads (Sec. 3.2, GQA)
+ *                                      hq / G, G = q_heads / kv_heads (Sec. 3.2, GQA); strides in
+ *                                      `rkv_params` (e.g. a query cache laid out [P, alpha, q_heads, d])
  *       k, v  [P, kv_heads, N, d]      token order = row order; strides in `rkv_params`
  *     fp32 / int32 outputs are dense: [P, kv_heads, n] or [P, kv_heads, budget].
  *   - P = num_problems independent (sequence, layer) pairs are processed per call.
@@ -51,7 +52,7 @@ typedef enum {
   RKV_ERR_SHAPE = -2,        /* inconsistent sizes: q_heads % kv_heads, budget <= alpha, N <= alpha, strides */
   RKV_ERR_UNSUPPORTED = -3,  /* outside the supported shapes listed above, or unknown flag bits */
   RKV_ERR_WORKSPACE = -4,    /* ws is NULL, misaligned or smaller than rkv_workspace_size() */
-  RKV_ERR_PARAM = -5,        /* lambda or sim_threshold outside [0, 1], beta < 0, eps < 0, pool_w < 0 */
+  RKV_ERR_PARAM = -5,        /* lambda or sim_threshold outside [0, 1], beta < 0, eps <= 0, pool_w < 0 */
   RKV_ERR_HIP = -6           /* a kernel launch failed (hipGetLastError) */
 } rkv_status;
 
@@ -106,11 +107,14 @@ typedef struct {
   int32_t beta;              /* most recent similar tokens whose similarity is zeroed (Sec. 3.3) */
   float   sim_threshold;     /* T, strict '>' (Sec. 3.3) */
   float   lambda;            /* trade-off of Eq. 7 (paper: 0.1) */
-  float   eps;               /* added to the key norm (Eq. 5, paper: 1e-8) */
+  float   eps;               /* added to the key norm (Eq. 5, paper: 1e-8); must be > 0, which is what keeps an
+                                all-zero key row finite (its similarities are then 0) */
   uint32_t flags;            /* 0 or RKV_FLAG_* bits */
   int64_t k_stride_problem, k_stride_head, k_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
   int64_t v_stride_problem, v_stride_head, v_stride_token;   /* in elements; 0,0,0 = dense [P,H,N,d] */
   int64_t o_stride_problem, o_stride_head, o_stride_token;   /* of k_out and v_out; 0,0,0 = dense [P,H,budget,d] */
+  int64_t q_stride_problem, q_stride_head, q_stride_token;   /* of q_obs / the query cache, in elements: problem, query
+                                                                head, window slot; 0,0,0 = dense [P,q_heads,alpha,d] */
   int32_t page_size;         /* 0 = contiguous caches; 16, 32, 64 or 128 tokens per page otherwise */
   int32_t table_stride;      /* entries of block_table per problem, >= ceil(N / page_size) */
   const int32_t* block_table;/* DEVICE pointer, int32 [P, table_stride] page indices (paged caches only) */

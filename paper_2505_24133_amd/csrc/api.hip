@@ -3,10 +3,31 @@
 #include <math.h>
 
 #include <algorithm>
+#include <atomic>
 
 #include "rkv_internal.h"
 
 namespace rkv {
+
+// Compute units of the current device, queried once per device ordinal and kept (256, the MI355X, when
+// no device is present: host-only use of the size query).
+int device_compute_units() {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<int> cached[kMaxDevices];          // 0 = not asked yet
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  int cus = cached[dev].load(std::memory_order_relaxed);
+  if (cus > 0) return cus;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+    (void)hipGetLastError();
+    cus = 256;
+  }
+  cached[dev].store(cus, std::memory_order_relaxed);
+  return cus;
+}
 
 static constexpr uint32_t kGqaFlags = RKV_FLAG_GQA_SOFTMAX_THEN_MAX | RKV_FLAG_GQA_SOFTMAX_THEN_MEAN;
 static constexpr uint32_t kKnownFlags =
@@ -27,7 +48,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   if (q.alpha > kMaxQRows || (int64_t)G * q.alpha > kMaxQRows || q.n_tokens > 32768) return RKV_ERR_UNSUPPORTED;
   if ((int64_t)q.num_problems * q.kv_heads > (1 << 22)) return RKV_ERR_UNSUPPORTED;
   if (!(q.lambda >= 0.f && q.lambda <= 1.f) || !(q.sim_threshold >= 0.f && q.sim_threshold <= 1.f) ||
-      !(q.eps >= 0.f) || !isfinite(q.eps) || q.beta < 0 || q.pool_w < 0 || (q.flags & kGqaFlags) == kGqaFlags)
+      !(q.eps > 0.f) || !isfinite(q.eps) || q.beta < 0 || q.pool_w < 0 || (q.flags & kGqaFlags) == kGqaFlags)
     return RKV_ERR_PARAM;
   const int64_t pool_rows = q.alpha + ((q.flags & RKV_FLAG_POOL_AFTER_MEAN) ? 1 : 0);
   if (pool_rows * (q.pool_w > 0 ? 2 * (int64_t)q.pool_w : 1) > 16384 || q.pool_w > 1000) return RKV_ERR_UNSUPPORTED;
@@ -77,6 +98,17 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   };
   if (!strides(q.k_stride_problem, q.k_stride_head, q.k_stride_token, &pl->ksp, &pl->ksh, &pl->kst)) return RKV_ERR_SHAPE;
   if (!strides(q.v_stride_problem, q.v_stride_head, q.v_stride_token, &pl->vsp, &pl->vsh, &pl->vst)) return RKV_ERR_SHAPE;
+  // observation queries [P, q_heads, alpha, d]: 0,0,0 = dense; otherwise rows 16-byte aligned, slots of a
+  // head and heads of a problem apart by the given strides
+  if (q.q_stride_problem == 0 && q.q_stride_head == 0 && q.q_stride_token == 0) {
+    pl->qst = kHeadDim; pl->qsh = (int64_t)q.alpha * kHeadDim; pl->qsp = pl->qsh * q.q_heads;
+  } else {
+    const int64_t st = q.q_stride_token, sh = q.q_stride_head, sp = q.q_stride_problem;
+    if (st < kHeadDim || (st % 8) != 0 || (sh % 8) != 0 || (sp % 8) != 0 || sh < 0 || sp < 0) return RKV_ERR_SHAPE;
+    if (q.q_heads > 1 && sh == 0) return RKV_ERR_SHAPE;
+    if (q.num_problems > 1 && sp == 0) return RKV_ERR_SHAPE;
+    pl->qst = st; pl->qsh = sh; pl->qsp = sp;
+  }
   if (q.o_stride_problem == 0 && q.o_stride_head == 0 && q.o_stride_token == 0) {
     pl->ost = kHeadDim; pl->osh = (int64_t)q.budget * kHeadDim; pl->osp = pl->osh * q.kv_heads;
   } else {
@@ -85,19 +117,19 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
 
   // ---- how the similarity pass is cut into workgroups (two are resident per compute unit): when the
   // row blocks of all heads would leave most of the machine idle, the column scan of every row block
-  // is split over several workgroups
+  // is split over several workgroups.  The workspace is sized for the largest split any device could
+  // choose (parts_reserved), so the size query does not depend on the device that is current.
+  int parts_reserved = 1;
   {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
-      (void)hipGetLastError();          // no device (host-only use of the size query): assume the MI355X
-      cus = 256;
-    }
-    const int64_t slots = 2 * cus;
     const int64_t blocks = (int64_t)pl->heads * ((pl->n + kGramRows - 1) / kGramRows);
     const int nct = (pl->n + kGramTile - 1) / kGramTile;
     pl->gram_parts = 1;
-    if (pl->beta == 1 && !pl->recency_transposed && blocks > 0 && blocks <= slots / 2)
-      pl->gram_parts = (int)std::max<int64_t>(1, std::min<int64_t>(std::min(nct, 16), slots / blocks));
+    if (pl->beta == 1 && !pl->recency_transposed && blocks > 0 && blocks <= kGramSplitMaxBlocks) {
+      parts_reserved = std::min(nct, kGramMaxParts);
+      const int64_t slots = 2 * (int64_t)device_compute_units();
+      if (blocks <= slots / 2)
+        pl->gram_parts = (int)std::max<int64_t>(1, std::min<int64_t>(parts_reserved, slots / blocks));
+    }
   }
 
   size_t off = 0;
@@ -112,7 +144,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->off_red = take(heads * np * 4);
   pl->off_z = take(heads * np * 4);
   pl->off_credit = take(pl->recency_transposed ? heads * np * 8 : 0);
-  const size_t parts = (size_t)pl->gram_parts;
+  const size_t parts = (size_t)parts_reserved;
   pl->off_pcnt = take(parts > 1 ? heads * parts * np * 4 : 0);
   pl->off_ppre = take(parts > 1 ? heads * parts * np * 4 : 0);
   pl->off_kdense = take(pl->paged ? heads * np * kHeadDim * 2 : 0);
@@ -128,6 +160,7 @@ static rkv_status check_ws(const Plan& pl, const void* ws, size_t ws_bytes) {
 }
 
 static rkv_status hip_status(hipError_t e) { return e == hipSuccess ? RKV_OK : RKV_ERR_HIP; }
+
 
 // An empty batch (num_problems == 0) is valid and enqueues nothing.
 static bool empty(const Plan& pl) { return pl.heads == 0; }

@@ -15,6 +15,7 @@ struct AppendArgs {
   const uint16_t* v_new;
   const uint16_t* q_new;
   int H, Hq, alpha, pos, slot, kv_rows, q_rows;
+  int64_t qsp, qsh, qst;      // strides of the query cache (elements): problem, query head, slot
   KvLayout kl, vl;
 };
 
@@ -30,7 +31,8 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
   } else if (row < a.kv_rows + a.q_rows) {                 // one row per (problem, query head)
     const int qr = row - a.kv_rows;
     const uint4 qx = *reinterpret_cast<const uint4*>(a.q_new + (int64_t)qr * kHeadDim + c16 * 8);
-    *reinterpret_cast<uint4*>(a.q_ring + ((int64_t)qr * a.alpha + a.slot) * kHeadDim + c16 * 8) = qx;
+    const int p = qr / a.Hq, hq = qr - p * a.Hq;
+    *reinterpret_cast<uint4*>(a.q_ring + p * a.qsp + hq * a.qsh + a.slot * a.qst + c16 * 8) = qx;
   }
 }
 
@@ -48,6 +50,7 @@ hipError_t launch_append(const Plan& pl, void* k_cache, void* v_cache, void* q_r
   a.H = pl.H; a.Hq = pl.H * pl.G; a.alpha = pl.alpha; a.pos = pos; a.slot = slot;
   a.kv_rows = pl.heads;
   a.q_rows = pl.P * pl.H * pl.G;
+  a.qsp = pl.qsp; a.qsh = pl.qsh; a.qst = pl.qst;
   a.kl = k_layout(pl); a.vl = v_layout(pl);
   const int threads = (a.kv_rows + a.q_rows) * 16;
   hipLaunchKernelGGL(append_kernel, dim3((threads + 255) / 256), dim3(256), 0, stream, a);

@@ -504,8 +504,7 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
     const int win = pl.W > 0 ? 2 * pl.W : 1;
     const size_t want = (size_t)a.pool_rows * (size_t)(pl.n + 3 + win);
     const size_t least = (size_t)a.pool_rows * (size_t)(win + 4); // four columns per block at the very least
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
+    const int cus = device_compute_units();
     const size_t cap = (pl.heads <= cus) ? kMaxPoolFloatsFewHeads : kMaxPoolFloats;
     size_t pool = std::min(std::max(want, least), cap);
     if (pool < least) return hipErrorInvalidValue;                // rejected earlier by make_plan

@@ -23,6 +23,8 @@
 
 #include "rkv_internal.h"
 
+#include "gram_index.h"
+
 namespace rkv {
 
 namespace {
@@ -53,19 +55,18 @@ __device__ __forceinline__ int slot_offset(int row, int chunk) { return row * kR
 // One wave-wide DMA copy: lane l fetches 16 bytes at base + voff and the hardware stores them
 // at LDS address lds_base + 16 * l.  Issued as inline assembly so that the compiler does not
 // serialise later LDS reads of the *other* buffer behind it; completion is awaited explicitly
-// (vmcnt) before the barrier that publishes the buffer.  M0 is written here; the compiler keeps no
-// value in M0 across statements on this target (it sets M0 immediately before each of its own uses).
+// (vmcnt) before the barrier that publishes the buffer.  M0 is written here and declared clobbered.
 __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_base), "v"(voff), "s"(base)
-               : "memory");
+               : "memory", "m0");
 }
 __device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2"
                :
                : "s"(lds_base), "v"(voff), "s"(base)
-               : "memory");
+               : "memory", "m0");
 }
 
 // Kernel variants (the common one carries none of the others' code):
@@ -157,24 +158,26 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   // Copy tile `ct` (keys ct*TC ...) and its r_j into buffer `buf`.  Keys past n are read from
   // row n-1 (any finite row will do: their r_j is 0).
   // One wave-wide DMA copy (4 rows) of tile `ct` into buffer `buf`; each wave issues LOADS / NW of them.
-  // Only the last tile can reach past n (CLAMP); for the others the row part of the address is
-  // wave-uniform and goes into the scalar base, leaving one per-lane offset register.
+  // Only a part's first tile can reach past n through a copy that is read (CLAMP); for the others the row
+  // part of the address is wave-uniform and goes into the scalar base, leaving one per-lane offset
+  // register.  gram_index.h holds the row arithmetic (and says why no row index reaches n).
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const uint32_t lane_row_bytes = (uint32_t)gram_copy_lane_row(lane, n) * row_bytes;
   auto issue_rows = [&](int ct, int buf, int jj, auto clamp) {
     const int row0 = (wave_s + jj * NW) * 4;                   // first of the 4 rows, inside the tile
     const uint32_t dst = lds0 + OFF_TILE + buf * TILE_SPAN + row0 * kRowBytes;
     const int chunk = (lane & 15) ^ ((row0 + (lane >> 4)) & 15);   // the chunk that belongs in this lane's slot
     if constexpr (decltype(clamp)::value) {
-      const int key = min(ct * TC + row0 + (lane >> 4), n - 1);
+      const int key = gram_copy_row_clamped(ct, TC, row0, lane, n);
       dma16(kbase, (uint32_t)key * row_bytes + (uint32_t)chunk * 16u, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
     } else {
-      const uint64_t addr = (uint64_t)(uintptr_t)kbase + (uint64_t)(uint32_t)(ct * TC + row0) * row_bytes;
+      const uint64_t addr = (uint64_t)(uintptr_t)kbase + (uint64_t)(uint32_t)gram_copy_first_row(ct, TC, row0, n) * row_bytes;
       // wave-uniform by construction; readfirstlane returns a signed int, so each half is narrowed to
       // uint32_t before widening (a sign-extended low half would overwrite the high half)
       const uint32_t addr_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(addr >> 32));
       const uint32_t addr_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
       const uint64_t addr_s = ((uint64_t)addr_hi << 32) | (uint64_t)addr_lo;
-      dma16(reinterpret_cast<const void*>(addr_s), (uint32_t)(lane >> 4) * row_bytes + (uint32_t)chunk * 16u,
+      dma16(reinterpret_cast<const void*>(addr_s), lane_row_bytes + (uint32_t)chunk * 16u,
             (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
     }
   };
@@ -190,8 +193,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   };
   // this workgroup's share of the column tiles: [ct_lo, ct_hi), scanned from ct_hi - 1 downwards
   const int nct_all = (a.beta > 0) ? (n + TC - 1) / TC : 0;
-  const int ct_lo = (int)((int64_t)part * nct_all / parts);
-  const int ct_hi = (int)((int64_t)(part + 1) * nct_all / parts);
+  int ct_lo, ct_hi;
+  gram_part_range(part, parts, nct_all, &ct_lo, &ct_hi);
   const int nct = ct_hi - ct_lo;
   const bool split = parts > 1;
   const bool closing = part == parts - 1;           // the part that also writes the closed-form row sums
@@ -435,8 +438,9 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     const int ct = ct_hi - 1 - it;
     const int buf = it & 1;
     // The next tile is copied while this one is used.  The last iteration copies its own tile once more
-    // (harmless, never read) so that the copy needs no branch inside the MFMA/VALU pipeline below.
-    const int ctn = max(ct - 1, ct_lo);
+    // (never read; rows pulled back inside [0, n) if the tile is partly filled) so that the copy needs no
+    // branch inside the MFMA/VALU pipeline below.
+    const int ctn = gram_next_tile(ct, ct_lo);
     issue_rj(ctn, buf ^ 1);
     const unsigned char* tile = gram_lds + OFF_TILE + buf * TILE_SPAN;
     const float* rjs = reinterpret_cast<const float*>(gram_lds + OFF_RJ + buf * TC * 4);

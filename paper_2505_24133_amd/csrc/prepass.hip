@@ -34,6 +34,7 @@ struct PrepassArgs {
   uint16_t* kdense;           // [heads][n_pad][128] dense copy of the candidate keys (paged caches), or nullptr
   int out_rows, out_groups;   // rows written per key: alpha (max over out_groups = G heads) or G*alpha (out_groups = 1)
   int64_t ksp, ksh, kst;
+  int64_t qsp, qsh, qst;      // strides of q (elements): problem, query head, window slot
   float eps, scale;
 };
 
@@ -103,13 +104,16 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
   bf16x8 qf[MT][8];
   if constexpr (HAS_Q) {
     const int GA = a.G * a.alpha;
-    const uint16_t* qbase = a.q + ((int64_t)p * a.H * a.G + (int64_t)h * a.G) * a.alpha * kHeadDim;
+    const uint16_t* qbase = a.q + p * a.qsp + (int64_t)h * a.G * a.qsh;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
+      // query row g * alpha + j of the group: head h * G + g, window slot j
       const int qrow = min(mt * 32 + (lane & 31), GA - 1);
+      const int qg = qrow / a.alpha;
+      const uint16_t* qr = qbase + qg * a.qsh + (qrow - qg * a.alpha) * a.qst;
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
-        const uint4 qv = *reinterpret_cast<const uint4*>(qbase + qrow * kHeadDim + kk * 16 + (lane >> 5) * 8);
+        const uint4 qv = *reinterpret_cast<const uint4*>(qr + kk * 16 + (lane >> 5) * 8);
         __builtin_memcpy(&qf[mt][kk], &qv, 16);
       }
     }
@@ -276,11 +280,10 @@ __global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a)
 template <bool HAS_Q, int MT, int AH, bool PAGED>
 void launch_paged(const PrepassArgs& a, hipStream_t stream) {
   static const int res = [] {
-    int per_cu = 0, dev = 0, cus = 0;
+    int per_cu = 0;
     const void* fn = reinterpret_cast<const void*>(&prepass_kernel<HAS_Q, MT, AH, PAGED>);
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kPrepassThreads, 0) != hipSuccess || per_cu < 1) per_cu = 2;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
-    return per_cu * cus;
+    return per_cu * device_compute_units();
   }();
   // a multiple of 8 workgroups, at most one per item of the XCD with the most heads
   const int per_xcd = std::max(1, std::min(((a.items / a.chunks + 7) / 8) * a.chunks, res / 8));
@@ -320,6 +323,7 @@ hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char
   a.page_shift = pl.page_shift; a.table_stride = pl.table_stride; a.kspage = pl.kspage;
   a.kdense = pl.paged ? reinterpret_cast<uint16_t*>(ws + pl.off_kdense) : nullptr;
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
+  a.qsp = pl.qsp; a.qsh = pl.qsh; a.qst = pl.qst;
   a.eps = pl.eps;
   a.scale = 1.0f / sqrtf((float)kHeadDim);
   a.items = pl.heads * pl.chunks;

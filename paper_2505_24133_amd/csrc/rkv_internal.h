@@ -14,6 +14,8 @@ constexpr int kChunk = 128;          // keys per workgroup in the key pre-pass
 constexpr int kMaxQRows = 64;        // G * alpha rows of observation queries per KV head
 constexpr int kGramRows = 256;       // candidate rows per workgroup of the similarity pass
 constexpr int kGramTile = 128;       // keys per streamed column tile of the similarity pass
+constexpr int kGramMaxParts = 16;    // most workgroups that share the column scan of one row block
+constexpr int kGramSplitMaxBlocks = 256;   // the scan is split only when all heads have at most this many row blocks
 constexpr int kRowBytes = kHeadDim * 2;
 constexpr int kLdsRowBytes = kRowBytes + 16;   // padded LDS row: 16-byte fragments of 8 consecutive rows hit distinct banks
 
@@ -53,6 +55,7 @@ struct Plan {
   int64_t ksp, ksh, kst;   // key strides (elements)
   int64_t vsp, vsh, vst;   // value strides (elements)
   int64_t osp, osh, ost;   // strides of the compacted outputs (elements)
+  int64_t qsp, qsh, qst;   // strides of the observation queries (elements): problem, query head, window slot
   bool paged;              // page_size > 0
   int page_shift, table_stride;
   const int32_t* block_table;
@@ -76,6 +79,7 @@ struct Plan {
 };
 
 rkv_status make_plan(const rkv_params* prm, Plan* plan);
+int device_compute_units();   // of the current device; cached after the first query
 
 // Kernel launchers (each enqueues on `stream` and returns hipGetLastError()).
 // Non-zero (alpha / 2, plus 100 with two query row tiles) when the pre-pass merges the group's heads in

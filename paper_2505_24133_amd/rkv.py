@@ -43,6 +43,7 @@ class RkvParams(ctypes.Structure):
         ("k_stride_problem", ctypes.c_int64), ("k_stride_head", ctypes.c_int64), ("k_stride_token", ctypes.c_int64),
         ("v_stride_problem", ctypes.c_int64), ("v_stride_head", ctypes.c_int64), ("v_stride_token", ctypes.c_int64),
         ("o_stride_problem", ctypes.c_int64), ("o_stride_head", ctypes.c_int64), ("o_stride_token", ctypes.c_int64),
+        ("q_stride_problem", ctypes.c_int64), ("q_stride_head", ctypes.c_int64), ("q_stride_token", ctypes.c_int64),
         ("page_size", ctypes.c_int32), ("table_stride", ctypes.c_int32), ("block_table", ctypes.c_void_p),
         ("k_stride_page", ctypes.c_int64), ("v_stride_page", ctypes.c_int64),
     ]
@@ -112,10 +113,12 @@ class Shape:
     block_table: Optional[torch.Tensor] = field(default=None, compare=False, repr=False)
 
     def params(self, k: Optional[torch.Tensor] = None, v: Optional[torch.Tensor] = None,
-               out: Optional[torch.Tensor] = None) -> RkvParams:
+               out: Optional[torch.Tensor] = None, q: Optional[torch.Tensor] = None) -> RkvParams:
         p = RkvParams(self.num_problems, self.kv_heads, self.q_heads, self.n_tokens, self.head_dim, self.alpha,
                       self.budget, self.pool_w, self.beta, self.sim_threshold, self.lam, self.eps, self.flags,
-                      0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, None, 0, 0)
+                      0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, None, 0, 0)
+        if q is not None and not q.is_contiguous():
+            p.q_stride_problem, p.q_stride_head, p.q_stride_token = q.stride(0), q.stride(1), q.stride(2)
         if self.page_size:
             bt = self.block_table
             if bt is None or bt.dtype != torch.int32 or not bt.is_cuda or not bt.is_contiguous() or bt.dim() != 2 \
@@ -172,8 +175,8 @@ def _check_kv(shape: Shape, t: torch.Tensor, what: str) -> None:
 
 def _check_q(shape: Shape, q: torch.Tensor) -> None:
     want = (shape.num_problems, shape.q_heads, shape.alpha, shape.head_dim)
-    if tuple(q.shape) != want or q.dtype != torch.bfloat16 or not q.is_contiguous():
-        raise ValueError(f"q_obs must be contiguous bf16 {want}")
+    if tuple(q.shape) != want or q.dtype != torch.bfloat16 or q.stride(3) != 1:
+        raise ValueError(f"q_obs must be bf16 {want} with a contiguous last dimension")
 
 
 def _check_out(shape: Shape, k_out: torch.Tensor, v_out: torch.Tensor) -> None:
@@ -206,7 +209,7 @@ def rkv_cache_append(shape: Shape, k_cache: torch.Tensor, v_cache: torch.Tensor,
     for t, want in ((k_new, kv), (v_new, kv), (q_new, qs)):
         if tuple(t.shape) != want or t.dtype != torch.bfloat16 or not t.is_contiguous():
             raise ValueError(f"new rows must be contiguous bf16 {want}")
-    prm = shape.params(k_cache, v_cache)
+    prm = shape.params(k_cache, v_cache, q=q_cache)
     s = load_library().rkv_cache_append(ctypes.byref(prm), _ptr(k_cache), _ptr(v_cache), _ptr(q_cache), _ptr(k_new),
                                         _ptr(v_new), _ptr(q_new), int(position), int(q_slot), _stream())
     if s != RKV_OK:
@@ -242,7 +245,7 @@ def rkv_score_importance(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, ws:
     if out is None:
         out = torch.empty((shape.num_problems, shape.kv_heads, shape.n_cand), dtype=torch.float32, device=k.device)
     ws, wp, wb = _ws_args(shape, ws, k.device)
-    prm = shape.params(k)
+    prm = shape.params(k, q=q_obs)
     s = load_library().rkv_score_importance(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(out), wp, wb, _stream())
     if s != RKV_OK:
         raise RkvError(s, "rkv_score_importance")
@@ -338,7 +341,7 @@ def rkv_compress_inplace(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: 
     if score is None and want_score:
         score = torch.empty((shape.num_problems, shape.kv_heads, shape.n_cand), dtype=torch.float32, device=dev)
     ws, wp, wb = _ws_args(shape, ws, dev)
-    prm = shape.params(k, v)
+    prm = shape.params(k, v, q=q_obs)
     s = load_library().rkv_compress_inplace(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(kept_idx),
                                             _ptr(score), wp, wb, _stream())
     if s < 0:
@@ -370,7 +373,7 @@ def rkv_compress(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Te
         score = torch.empty((shape.num_problems, shape.kv_heads, shape.n_cand), dtype=torch.float32, device=dev)
     ws, wp, wb = _ws_args(shape, ws, dev)
     _check_out(shape, k_out, v_out)
-    prm = shape.params(k, v, k_out)
+    prm = shape.params(k, v, k_out, q=q_obs)
     lib = load_library()
     if events is None:
         s = lib.rkv_compress(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out),
@@ -381,3 +384,4 @@ def rkv_compress(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Te
     if s < 0:
         raise RkvError(s, "rkv_compress")
     return s, k_out, v_out, kept_idx, score
+

@@ -48,7 +48,7 @@ def test_params_struct_layout_matches_header(repo_root, tmp_path):
     out = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     assert out[0] == ctypes.sizeof(rkv.RkvParams)
     assert out[1:] == [getattr(rkv.RkvParams, n).offset for n in names]
-    assert rkv.RkvParams.k_stride_problem.offset == 56 and rkv.RkvParams.page_size.offset == 56 + 9 * 8
+    assert rkv.RkvParams.k_stride_problem.offset == 56 and rkv.RkvParams.page_size.offset == 56 + 12 * 8
 
 
 def shape(**kw):
@@ -92,6 +92,19 @@ def test_workspace_size_and_validation(lib):
     assert ws_status(lib, shape(beta=-1))[0] == rkv.RKV_ERR_PARAM
     assert ws_status(lib, shape(pool_w=-1))[0] == rkv.RKV_ERR_PARAM
     assert ws_status(lib, shape(eps=-1.0))[0] == rkv.RKV_ERR_PARAM
+    assert ws_status(lib, shape(eps=0.0))[0] == rkv.RKV_ERR_PARAM                  # Eq. 5's eps is what keeps a zero key finite
+    assert ws_status(lib, shape(eps=float("inf")))[0] == rkv.RKV_ERR_PARAM
+    # observation queries: dense by default, or strided rows (16-byte aligned)
+    def qs(sp, sh, st):
+        p = shape().params()
+        p.q_stride_problem, p.q_stride_head, p.q_stride_token = sp, sh, st
+        n = ctypes.c_size_t(0)
+        return lib.rkv_workspace_size(ctypes.byref(p), ctypes.byref(n))
+    assert qs(8 * 32 * 128, 128, 32 * 128) == rkv.RKV_OK                           # [P, alpha, q_heads, d]
+    assert qs(8 * 32 * 128, 128, 100) == rkv.RKV_ERR_SHAPE
+    assert qs(8 * 32 * 128, 0, 32 * 128) == rkv.RKV_ERR_SHAPE
+    assert qs(0, 128, 32 * 128) == rkv.RKV_ERR_SHAPE
+    assert qs(8 * 32 * 128, 132, 32 * 128) == rkv.RKV_ERR_SHAPE
     assert lib.rkv_workspace_size(None, ctypes.byref(ctypes.c_size_t(0))) == rkv.RKV_ERR_NULL
 
 
