@@ -191,6 +191,24 @@ rkv_status rkv_compress_inplace(const rkv_params* prm, const void* q_obs, void* 
                                 float* score, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * rkv_compress for callers that cannot allocate device memory or pass a workspace: code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without ws),
+ * same kernels, same results bit for bit and same statuses as rkv_compress; the scratch is a fixed array of
+ * RKV_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on until the process ends.  The call
+ * allocates and frees nothing, sets no memory with a runtime call and does not synchronise; the first call
+ * on each GPU looks the array's address up once (make that call before a capture starts).
+ *   - Shapes whose rkv_workspace_size() exceeds RKV_STATIC_SCRATCH_BYTES return RKV_ERR_WORKSPACE with
+ *     nothing enqueued (the limit covers one sequence of the 8B model at budget 1024: 32 layers x 8 heads,
+ *     N = 1152, about 18 MiB).
+ *   - All calls on one GPU share that GPU's array, whatever their stream: calls that overlap in time on one
+ *     GPU race and give unspecified results.  Calls on one stream, or ordered by events, are safe; the
+ *     array needs no clearing between calls.
+ */
+#define RKV_STATIC_SCRATCH_BYTES (32u << 20)
+rkv_status rkv_compress_static(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
+                               void* k_out, void* v_out, int32_t* kept_idx, float* score, void* stream);
+
+/*
  * Instrumented form of rkv_compress for measurement: identical work, and additionally records the
  * five caller-created hipEvent_t handles events[0..4] (a HOST array) on `stream` before the key
  * pre-pass and after the pre-pass, the similarity pass, the finalize/select kernel and the gather,

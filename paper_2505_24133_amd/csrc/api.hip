@@ -161,6 +161,32 @@ static rkv_status check_ws(const Plan& pl, const void* ws, size_t ws_bytes) {
 
 static rkv_status hip_status(hipError_t e) { return e == hipSuccess ? RKV_OK : RKV_ERR_HIP; }
 
+// Scratch of rkv_compress_static: one array per GPU, held from the moment the library's code is loaded on
+// that GPU until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address kernels and copies use is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[RKV_STATIC_SCRATCH_BYTES];
+
+static rkv_status static_scratch(char** out) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> address[kMaxDevices];       // nullptr = not looked up yet on that device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return RKV_ERR_HIP;
+  }
+  void* p = address[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    // with device `dev` current this returns the address of that device's copy of the array; two threads
+    // racing here look up the same value
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return RKV_ERR_HIP;
+    }
+    address[dev].store(p, std::memory_order_release);
+  }
+  *out = static_cast<char*>(p);
+  return RKV_OK;
+}
 
 // An empty batch (num_problems == 0) is valid and enqueues nothing.
 static bool empty(const Plan& pl) { return pl.heads == 0; }
@@ -298,6 +324,20 @@ rkv_status rkv_compress(const rkv_params* prm, const void* q_obs, const void* k,
                         void* k_out, void* v_out, int32_t* kept_idx, float* score,
                         void* ws, size_t ws_bytes, void* stream) {
   return compress_impl(prm, q_obs, k, v, k_out, v_out, kept_idx, score, ws, ws_bytes, stream, nullptr);
+}
+
+rkv_status rkv_compress_static(const rkv_params* prm, const void* q_obs, const void* k, const void* v,
+                               void* k_out, void* v_out, int32_t* kept_idx, float* score, void* stream) {
+  // validate and size first: a shape whose scratch does not fit is refused before anything is looked up
+  Plan pl;
+  rkv_status s = make_plan(prm, &pl);
+  if (s != RKV_OK) return s;
+  if (empty(pl)) return RKV_OK;
+  if (pl.total > (size_t)RKV_STATIC_SCRATCH_BYTES) return RKV_ERR_WORKSPACE;
+  char* ws = nullptr;
+  if (pl.N > pl.budget && (s = static_scratch(&ws)) != RKV_OK) return s;
+  if (ws == nullptr) ws = reinterpret_cast<char*>(256);          // not triggered: never dereferenced
+  return compress_impl(prm, q_obs, k, v, k_out, v_out, kept_idx, score, ws, (size_t)RKV_STATIC_SCRATCH_BYTES, stream, nullptr);
 }
 
 rkv_status rkv_compress_events(const rkv_params* prm, const void* q_obs, const void* k, const void* v,

@@ -30,6 +30,7 @@ RKV_FLAG_SHARED_SELECTION = 4
 RKV_FLAG_GQA_SOFTMAX_THEN_MAX = 8
 RKV_FLAG_GQA_SOFTMAX_THEN_MEAN = 16
 RKV_FLAG_RECENCY_TRANSPOSED = 32
+RKV_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class RkvParams(ctypes.Structure):
@@ -73,13 +74,14 @@ def load_library() -> ctypes.CDLL:
     lib.rkv_select_topk.argtypes = [P, V, V, V, V, V, S, V]
     lib.rkv_compact.argtypes = [P, V, V, V, V, V, V]
     lib.rkv_compress.argtypes = [P, V, V, V, V, V, V, V, V, S, V]
+    lib.rkv_compress_static.argtypes = [P, V, V, V, V, V, V, V, V]
     lib.rkv_compress_events.argtypes = [P, V, V, V, V, V, V, V, V, S, V, ctypes.POINTER(ctypes.c_void_p)]
     lib.rkv_compact_inplace.argtypes = [P, V, V, V, V]
     lib.rkv_compress_inplace.argtypes = [P, V, V, V, V, V, V, S, V]
     lib.rkv_should_compress.argtypes = [P, ctypes.c_int32]
     lib.rkv_cache_append.argtypes = [P, V, V, V, V, V, V, ctypes.c_int32, ctypes.c_int32, V]
     for name in ("rkv_workspace_size", "rkv_score_importance", "rkv_score_redundancy", "rkv_select_topk",
-                 "rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_should_compress", "rkv_cache_append",
+                 "rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_compress_static", "rkv_should_compress", "rkv_cache_append",
                  "rkv_compact_inplace", "rkv_compress_inplace"):
         getattr(lib, name).restype = ctypes.c_int
     lib.rkv_status_string.argtypes = [ctypes.c_int]
@@ -385,3 +387,23 @@ def rkv_compress(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Te
         raise RkvError(s, "rkv_compress")
     return s, k_out, v_out, kept_idx, score
 
+
+def rkv_compress_static(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Tensor, k_out: torch.Tensor,
+                        v_out: torch.Tensor, kept_idx: Optional[torch.Tensor] = None,
+                        score: Optional[torch.Tensor] = None) -> int:
+    """The whole step with the library's fixed scratch array instead of a workspace.  Every buffer is the
+    caller's; nothing is allocated here or in the library.  Returns RKV_OK or RKV_NOT_TRIGGERED; shapes whose
+    scratch exceeds RKV_STATIC_SCRATCH_BYTES raise (RKV_ERR_WORKSPACE)."""
+    _need_gpu(q_obs, k, v, k_out, v_out, kept_idx, score)
+    _check_q(shape, q_obs)
+    _check_kv(shape, k, "k")
+    _check_kv(shape, v, "v")
+    _check_out(shape, k_out, v_out)
+    if kept_idx is not None:
+        _check_idx(shape, kept_idx)
+    prm = shape.params(k, v, k_out, q=q_obs)
+    s = load_library().rkv_compress_static(ctypes.byref(prm), _ptr(q_obs), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out),
+                                           _ptr(kept_idx), _ptr(score), _stream())
+    if s < 0:
+        raise RkvError(s, "rkv_compress_static")
+    return s

@@ -25,7 +25,7 @@ def declared_symbols(repo_root):
 
 def test_every_declared_symbol_is_exported(lib, repo_root):
     names = declared_symbols(repo_root)
-    assert names == ["rkv_cache_append", "rkv_compact", "rkv_compact_inplace", "rkv_compress", "rkv_compress_events", "rkv_compress_inplace", "rkv_score_importance", "rkv_score_redundancy",
+    assert names == ["rkv_cache_append", "rkv_compact", "rkv_compact_inplace", "rkv_compress", "rkv_compress_events", "rkv_compress_inplace", "rkv_compress_static", "rkv_score_importance", "rkv_score_redundancy",
                      "rkv_select_topk", "rkv_should_compress", "rkv_status_string", "rkv_workspace_size"]
     for n in names:
         assert hasattr(lib, n), n
@@ -154,6 +154,29 @@ def test_null_and_workspace_errors_return_before_any_launch(lib):
     bad.k_stride_head = 8
     bad.k_stride_problem = 8
     assert lib.rkv_compress(ctypes.byref(bad), fake, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == rkv.RKV_ERR_SHAPE
+
+
+def test_static_scratch_entry_point_validates_on_the_host(lib):
+    """rkv_compress_static refuses what does not fit its fixed scratch, and what rkv_compress refuses,
+    before it looks anything up on a device."""
+    fake = ctypes.c_void_p(0x1000)
+    big = shape(num_problems=32, n_tokens=4224, budget=4096)
+    assert ws_status(lib, big)[1] > rkv.RKV_STATIC_SCRATCH_BYTES
+    p = big.params()
+    assert lib.rkv_compress_static(ctypes.byref(p), fake, fake, fake, fake, fake, None, None, None) == rkv.RKV_ERR_WORKSPACE
+    fits = shape(num_problems=32)
+    assert 0 < ws_status(lib, fits)[1] <= rkv.RKV_STATIC_SCRATCH_BYTES          # one sequence of the 8B model, budget 1024
+    p = fits.params()
+    assert lib.rkv_compress_static(ctypes.byref(p), None, fake, fake, fake, fake, None, None, None) in (rkv.RKV_ERR_NULL, rkv.RKV_ERR_HIP)
+    p = shape(n_tokens=1024, budget=1024).params()
+    assert lib.rkv_compress_static(ctypes.byref(p), fake, fake, fake, fake, fake, None, None, None) == rkv.RKV_NOT_TRIGGERED
+    p = shape(eps=0.0).params()
+    assert lib.rkv_compress_static(ctypes.byref(p), fake, fake, fake, fake, fake, None, None, None) == rkv.RKV_ERR_PARAM
+    assert lib.rkv_compress_static(None, fake, fake, fake, fake, fake, None, None, None) == rkv.RKV_ERR_NULL
+    p = shape(num_problems=0).params()
+    assert lib.rkv_compress_static(ctypes.byref(p), None, None, None, None, None, None, None, None) == rkv.RKV_OK
+    header = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "rkv.h")).read()
+    assert "#define RKV_STATIC_SCRATCH_BYTES (32u << 20)" in header and rkv.RKV_STATIC_SCRATCH_BYTES == 32 << 20
 
 
 def test_status_strings(lib):
