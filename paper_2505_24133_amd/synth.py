@@ -201,8 +201,57 @@ def make_problem(w: Workload, p: int) -> Tuple[np.ndarray, np.ndarray, np.ndarra
     return f32_to_bf16_bits(q), kb, f32_to_bf16_bits(v)
 
 
-def make_batch(w: Workload, problems: Iterable[int] | None = None):
-    """Stack problems: q [P,Hq,alpha,d], k [P,H,N,d], v [P,H,N,d] (uint16 bf16 bits)."""
+def _batch_shapes(w: Workload, count: int):
+    d = w.head_dim
+    return ((count, w.q_heads, w.alpha, d), (count, w.kv_heads, w.n_tokens, d), (count, w.kv_heads, w.n_tokens, d))
+
+
+def _fill_task(args):
+    """Worker of ``make_batch(..., workers > 1)``: draw some problems into the shared files."""
+    w, paths, count, todo = args
+    maps = [np.memmap(path, dtype=np.uint16, mode="r+", shape=shape) for path, shape in zip(paths, _batch_shapes(w, count))]
+    for slot, p in todo:
+        for m, x in zip(maps, make_problem(w, p)):
+            m[slot] = x
+    for m in maps:
+        m.flush()
+    return len(todo)
+
+
+def make_batch(w: Workload, problems: Iterable[int] | None = None, workers: int = 1):
+    """Stack problems: q [P,Hq,alpha,d], k [P,H,N,d], v [P,H,N,d] (uint16 bf16 bits).
+
+    With ``workers`` > 1 the problems are drawn by that many CPU-only worker processes (spawned, so they
+    inherit nothing from a parent that uses the GPU) into memory-mapped scratch files that are unlinked
+    before the arrays are returned; the values are those of the serial path, problem by problem."""
     ps = list(range(w.num_problems)) if problems is None else list(problems)
-    qs, ks, vs = zip(*(make_problem(w, p) for p in ps))
-    return np.stack(qs), np.stack(ks), np.stack(vs)
+    if workers <= 1 or len(ps) < 2:
+        qs, ks, vs = zip(*(make_problem(w, p) for p in ps))
+        return np.stack(qs), np.stack(ks), np.stack(vs)
+    import multiprocessing as mp
+    import os
+    import tempfile
+    from concurrent.futures import ProcessPoolExecutor
+    workers = min(workers, len(ps))
+    base = "/dev/shm" if os.path.isdir("/dev/shm") and os.access("/dev/shm", os.W_OK) else None
+    paths = []
+    try:
+        for shape in _batch_shapes(w, len(ps)):
+            fd, path = tempfile.mkstemp(prefix="rkv_synth_", suffix=".u16", dir=base)
+            os.ftruncate(fd, int(np.prod(shape)) * 2)
+            os.close(fd)
+            paths.append(path)
+        todo = list(enumerate(ps))
+        tasks = [(w, paths, len(ps), todo[i::4 * workers]) for i in range(4 * workers) if todo[i::4 * workers]]
+        with ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn")) as ex:
+            done = sum(ex.map(_fill_task, tasks))
+        assert done == len(ps)
+        out = tuple(np.memmap(path, dtype=np.uint16, mode="r+", shape=shape)
+                    for path, shape in zip(paths, _batch_shapes(w, len(ps))))
+    finally:
+        for path in paths:                      # the mappings above stay valid; the files hold no name any more
+            try:
+                os.unlink(path)
+            except OSError:
+                pass
+    return out

@@ -1,10 +1,15 @@
 """Host-side helpers for the parity tests: tolerance rules, detection of rows whose threshold
-decision is within rounding of T, exact top-k of a score vector.  CPU only, numpy only."""
+decision is within rounding of T, exact top-k of a score vector, and a pool of CPU-only worker
+processes that run the oracle on many heads at once.  CPU only, numpy only."""
 from __future__ import annotations
+
+import atexit
+import os
 
 import numpy as np
 
 from oracle import rkv_oracle as O
+from paper_2505_24133_amd import synth
 
 # Scores: |gpu - oracle| <= ABS_TOL + REL_TOL * |oracle| (fp32 accumulation vs the float64 oracle).
 REL_TOL = 1e-3
@@ -74,3 +79,108 @@ def check_kept_against_oracle(kept_sel: np.ndarray, z_ref: np.ndarray, k: int, s
     must_drop = (z_ref < tau - tol) & ~skip
     free = ~(must_keep | must_drop)
     return int((must_keep & ~kept_mask).sum()), int((must_drop & kept_mask).sum()), int(free.sum())
+
+
+# Error of the GPU's joint score relative to the size of its two terms, lambda |I| + (1 - lambda) |R|
+# (fp32 accumulation against the float64 oracle); the parity tests assert it for every candidate.
+TERM_REL_ERR = 5e-5
+
+
+def decidable_selection(z_ref: np.ndarray, err: np.ndarray, k: int):
+    """Which candidates the top-k MUST hold and which it MUST NOT, for any score vector z' with
+    |z' - z_ref| <= err element-wise (whatever the tie-break): candidate i is certainly kept when fewer
+    than k others can reach its lowest possible score, and certainly dropped when at least k others stay
+    above its highest possible score.  Returns (must_keep, must_drop) boolean masks; the rest is free."""
+    lo, hi = z_ref - err, z_ref + err
+    hi_sorted, lo_sorted = np.sort(hi), np.sort(lo)
+    n = z_ref.shape[0]
+    # others j with hi_j >= lo_i  (i itself always counts: hi_i >= lo_i)
+    can_reach = n - np.searchsorted(hi_sorted, lo, side="left") - 1
+    # others j with lo_j > hi_i   (i itself never counts)
+    stay_above = n - np.searchsorted(lo_sorted, hi, side="right")
+    return can_reach < k, stay_above >= k
+
+
+# ------------------------------------------------------------------ the oracle on many heads at once
+_POOL = None
+
+
+def oracle_workers() -> int:
+    """Worker processes for the oracle: the machine's CPU share (16 per GPU), less on smaller hosts."""
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def _pool():
+    """CPU-only worker processes (spawned, so they never inherit the parent's GPU state), started once."""
+    global _POOL
+    if _POOL is None:
+        import multiprocessing as mp
+        from concurrent.futures import ProcessPoolExecutor
+        _POOL = ProcessPoolExecutor(max_workers=oracle_workers(), mp_context=mp.get_context("spawn"),
+                                    initializer=_worker_init)
+        atexit.register(_POOL.shutdown, wait=False, cancel_futures=True)
+    return _POOL
+
+
+def _worker_init():
+    """The oracle allocates and frees n x n float64 matrices for every head.  Keeping freed memory in the
+    worker's heap (no mmap for large blocks, no trimming) spares the first-touch page faults of fresh
+    mappings, which otherwise take several times longer than the oracle's arithmetic."""
+    import ctypes
+    try:
+        libc = ctypes.CDLL("libc.so.6")
+        libc.mallopt(-4, 0)                  # M_MMAP_MAX = 0
+        libc.mallopt(-1, 2 ** 31 - 1)        # M_TRIM_THRESHOLD
+    except OSError:                          # pragma: no cover
+        pass
+
+
+def _single_thread():
+    try:
+        from threadpoolctl import threadpool_limits
+        return threadpool_limits(limits=1)
+    except Exception:                                   # pragma: no cover
+        import contextlib
+        return contextlib.nullcontext()
+
+
+def _oracle_heads_task(args):
+    """Worker: draw problem p of workload w from its seeded recipe and run the oracle on the heads hs."""
+    w, p, hs, variant = args
+    with _single_thread():
+        q, k, v = synth.make_problem(w, p)
+        prm = oracle_params(w, **variant)
+        G = w.group
+        return [(p, h, O.compress_head(q[h * G:(h + 1) * G], k[h], v[h], prm)) for h in hs]
+
+
+def oracle_heads(w, heads, **variant):
+    """Yield ((p, h), oracle dict) for the listed heads of a seeded workload, computed by the worker
+    pool (each worker regenerates its problems from the recipe; nothing comes from the GPU)."""
+    by_problem = {}
+    for (p, h) in heads:
+        by_problem.setdefault(p, []).append(h)
+    tasks = []
+    for p, hs in sorted(by_problem.items()):
+        for i in range(0, len(hs), 2):                  # at most two heads per task keeps the workers evenly loaded
+            tasks.append((w, p, hs[i:i + 2], variant))
+    from concurrent.futures import as_completed
+    futs = [_pool().submit(_oracle_heads_task, t) for t in tasks]
+    for f in as_completed(futs):
+        for (p, h, ref) in f.result():
+            yield (p, h), ref
+
+
+def _oracle_rows_task(args):
+    k_bits, rows, T, beta, eps = args
+    with _single_thread():
+        return O.mean_similarity_rows(O.decode_bf16(k_bits), rows, T, beta, eps)
+
+
+def mean_similarity_all_rows(k_bits: np.ndarray, T: float, beta: int, eps: float) -> np.ndarray:
+    """Eq. 5-6 for every candidate of a head too large for the n x n matrix: the oracle's row-by-row
+    form, the rows dealt to the worker pool."""
+    n = k_bits.shape[0]
+    parts = np.array_split(np.arange(n), 4 * oracle_workers())
+    futs = [_pool().submit(_oracle_rows_task, (k_bits, rows, T, beta, eps)) for rows in parts if len(rows)]
+    return np.concatenate([f.result() for f in futs])
