@@ -1066,7 +1066,7 @@ def test_bench_prints_one_json_line_with_the_agreed_fields(repo_root):
     import subprocess
     import sys
     say("bench.py --steps 3 (child process)")
-    r = subprocess.run([sys.executable, "bench.py", "--steps", "3", "--warmup", "1", "--no-other-modes", "--cpu-seconds", "1"],
+    r = subprocess.run([sys.executable, "bench.py", "--steps", "3", "--warmup", "1", "--no-other-modes", "--no-workloads", "--cpu-seconds", "1"],
                        cwd=repo_root, capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.strip()]
@@ -1082,6 +1082,12 @@ def test_bench_prints_one_json_line_with_the_agreed_fields(repo_root):
     assert roof["bound"] == "mfma" and roof["unit"] == "TFLOP/s" and roof["peak"] == 2500.0
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9 and 0.05 < roof["frac"] < 1.0
     assert roof["traffic"] is None or roof["traffic"] > 0
+    dev = d["device"]
+    assert dev["device_copy_GB/s"] > 500 and dev["published_peaks"]["hbm_GB/s"] == 8000.0
+    assert dev["clocks_under_load"] is None or 100 < dev["clocks_under_load"]["sclk_mhz"] <= 2600
+    cold = d["cold"]
+    assert cold["sets_rotated"] >= 2 and cold["bytes_between_reuse"] > 4 * (256 << 20) and cold["ms_per_step"] > 0
+    assert set(cold["stages"]) == set(d["stages"])
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["unit"] == d["unit"] and cpu["sample"]
 
