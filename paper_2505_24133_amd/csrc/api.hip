@@ -121,6 +121,9 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   // choose (parts_reserved), so the size query does not depend on the device that is current.
   int parts_reserved = 1;
   {
+    // (counted in row blocks of the dense kernel also for RKV_FLAG_SKIP_SATURATED, whose own row blocks are
+    // smaller: the two must take the same decision, because the split changes the order of the last few
+    // floating-point operations and the flag promises bit-identical results)
     const int64_t blocks = (int64_t)pl->heads * ((pl->n + kGramRows - 1) / kGramRows);
     const int nct = (pl->n + kGramTile - 1) / kGramTile;
     pl->gram_parts = 1;

@@ -41,7 +41,6 @@ struct GramArgs {
   float* part_pre;              // [heads][parts][n_pad] their sum
   int H, heads, n, n_pad, chunks, beta;
   int row_blocks, parts;        // workgroups per head = row_blocks * parts
-  int tail_last;                // narrow last row blocks are listed after all other workgroups
   int64_t ksp, ksh, kst;
   float T, eps;
 };
@@ -83,9 +82,10 @@ constexpr int kCompactBytes = 3072;             // SKIP: open-row counts of the 
 
 template <int NW, int RT, int TC, int WPS, int VARIANT, bool SKIP, bool B1>
 __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
-  // WPS = waves per SIMD the register budget is cut for: 2 keeps two sets of key fragments and r_j
-  // (prefetch one subtile ahead), 3 keeps one set and relies on the other waves to hide LDS latency.
-  constexpr int KB = (WPS >= 3) ? 1 : 2;
+  // WPS = waves per SIMD the register budget is cut for.  With two row tiles per wave there is room for two
+  // sets of key fragments and r_j (the next subtile's are fetched a step ahead); with three row tiles (or
+  // three waves per SIMD) one set is kept and refilled fragment by fragment behind the subtile's last chain.
+  constexpr int KB = (WPS >= 3 || RT >= 3) ? 1 : 2;
   constexpr int NT = NW * 64;
   constexpr int BM = NW * RT * 32;
   constexpr int NS = TC / 32;                       // 32-key subtiles per tile
@@ -102,32 +102,16 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   static_assert(64 + NW * 32 * 20 <= kCompactBytes && 2 * NW * 4 <= 64, "record area");
 
   // Workgroups are dealt round-robin to the 8 XCDs; give every XCD whole heads so that a head's
-  // keys are fetched into one L2 only.  A head's workgroups (row block x column part) are adjacent,
-  // except that narrow last row blocks (at most NW * 32 rows, about half the lifetime of the others)
-  // come after all the others: the launch then ends with short workgroups instead of full-length ones.
+  // keys are fetched into one L2 only.  A head's workgroups (row block x column part) are adjacent.
   const int b = blockIdx.x;
   const int xcd = b & 7;
-  int q = b >> 3;
+  const int q = b >> 3;
   const int parts = (VARIANT == kSplit) ? a.parts : 1;
-  const int head_groups = (a.heads + 7) >> 3;
-  const bool tail_last = (VARIANT != kSplit) && (WPS < 3) && a.tail_last != 0;
-  int head, rb, part;
-  if (!tail_last) {
-    const int per_head = a.row_blocks * parts;
-    head = (q / per_head) * 8 + xcd;
-    const int rem = q % per_head;
-    rb = rem / parts;
-    part = rem - rb * parts;
-  } else if (q < head_groups * (a.row_blocks - 1)) {
-    head = (q / (a.row_blocks - 1)) * 8 + xcd;
-    rb = q % (a.row_blocks - 1);
-    part = 0;
-  } else {
-    q -= head_groups * (a.row_blocks - 1);
-    head = q * 8 + xcd;
-    rb = a.row_blocks - 1;
-    part = 0;
-  }
+  const int per_head = a.row_blocks * parts;
+  const int head = (q / per_head) * 8 + xcd;
+  const int rem = q % per_head;
+  const int rb = rem / parts;
+  const int part = rem - rb * parts;
   if (head >= a.heads) return;
 
   const int t = threadIdx.x;
@@ -145,12 +129,14 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
       (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)kb64));
   const float* rn = a.rnorm + (int64_t)head * a.n_pad;
   const int n = a.n;
-  // A last row block with at most NW * 32 rows is "narrow": every wave takes one row tile of it instead
-  // of two waves taking two each, and the scan below runs with one chain per subtile, so the workgroup
-  // lives about half as long.  The second row tile of a wave then stands for rows past n.
-  const bool narrow = (KB == 2) && (n - rb * BM <= NW * 32);
-  const int i0 = rb * BM + wave * (narrow ? 32 : RT * 32);
-  const int tile_rows = narrow ? (1 << 20) : 32;     // row distance between a wave's row tiles
+  // Row tiles of this block that hold candidates, dealt to the waves in runs of `rte` tiles: a full block
+  // gives every wave RT tiles; a last block with fewer rows gives every wave fewer (its other row tiles
+  // stand for rows past n), and the scan below then runs with that many chains per subtile, so the
+  // workgroup lives correspondingly shorter.
+  const int rtc = min((n - rb * BM + 31) >> 5, NW * RT);
+  const int rte = (rtc + NW - 1) / NW;                 // 1 .. RT, the same for every wave of the workgroup
+  const int i0 = rb * BM + wave * rte * 32;
+  auto tile_row0 = [&](int rt) -> int { return rt < rte ? i0 + rt * 32 : (1 << 20); };   // first row of the wave's row tile rt
   bool active = i0 < n;                              // wave-uniform: does this wave own any candidate row?
   const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)gram_lds);   // LDS byte address of the dynamic segment
   const uint32_t row_bytes = (uint32_t)a.kst * 2u;
@@ -162,24 +148,31 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   // part of the address is wave-uniform and goes into the scalar base, leaving one per-lane offset
   // register.  gram_index.h holds the row arithmetic (and says why no row index reaches n).
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  const uint32_t lane_row_bytes = (uint32_t)gram_copy_lane_row(lane, n) * row_bytes;
-  auto issue_rows = [&](int ct, int buf, int jj, auto clamp) {
+  // chunk that belongs in this lane's LDS slot: rows wave*4 + jj*16 + lane/16 differ by multiples of 16 between
+  // the wave's copies, so the swizzle (row & 15) and with it the lane's byte offset is the same for all of them
+  const int lane_chunk = (lane & 15) ^ ((wave * 4 + (lane >> 4)) & 15);
+  auto issue_rows_clamped = [&](int ct, int buf, int jj) {
     const int row0 = (wave_s + jj * NW) * 4;                   // first of the 4 rows, inside the tile
     const uint32_t dst = lds0 + OFF_TILE + buf * TILE_SPAN + row0 * kRowBytes;
-    const int chunk = (lane & 15) ^ ((row0 + (lane >> 4)) & 15);   // the chunk that belongs in this lane's slot
-    if constexpr (decltype(clamp)::value) {
-      const int key = gram_copy_row_clamped(ct, TC, row0, lane, n);
-      dma16(kbase, (uint32_t)key * row_bytes + (uint32_t)chunk * 16u, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
-    } else {
-      const uint64_t addr = (uint64_t)(uintptr_t)kbase + (uint64_t)(uint32_t)gram_copy_first_row(ct, TC, row0, n) * row_bytes;
-      // wave-uniform by construction; readfirstlane returns a signed int, so each half is narrowed to
-      // uint32_t before widening (a sign-extended low half would overwrite the high half)
-      const uint32_t addr_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(addr >> 32));
-      const uint32_t addr_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
-      const uint64_t addr_s = ((uint64_t)addr_hi << 32) | (uint64_t)addr_lo;
-      dma16(reinterpret_cast<const void*>(addr_s), lane_row_bytes + (uint32_t)chunk * 16u,
-            (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
-    }
+    const int key = gram_copy_row_clamped(ct, TC, row0, lane, n);
+    dma16(kbase, (uint32_t)key * row_bytes + (uint32_t)lane_chunk * 16u, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
+  };
+  // Unclamped form, used inside the scan: per tile one scalar source pointer (the wave's first row of the
+  // tile) and one scalar LDS address; the wave's copies lie 16 rows apart in both.
+  const uint32_t lane_off = (uint32_t)gram_copy_lane_row(lane, n) * row_bytes + (uint32_t)lane_chunk * 16u;
+  const uint32_t group_step = (uint32_t)gram_copy_group_row(16, TC, n) * row_bytes;
+  auto tile_source = [&](int ct) -> uint64_t {
+    const int row = gram_copy_tile_row0(ct, TC, n) + gram_copy_group_row(wave_s * 4, TC, n);
+    const uint64_t addr = (uint64_t)(uintptr_t)kbase + (uint64_t)(uint32_t)row * row_bytes;
+    // wave-uniform by construction; readfirstlane returns a signed int, so each half is narrowed to
+    // uint32_t before widening (a sign-extended low half would overwrite the high half)
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(addr >> 32));
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
+    return ((uint64_t)hi << 32) | (uint64_t)lo;
+  };
+  auto issue_rows = [&](uint64_t src, uint32_t dst, int jj) {
+    dma16(reinterpret_cast<const void*>(src + (uint64_t)((uint32_t)jj * group_step)), lane_off,
+          dst + (uint32_t)(jj * NW * 4 * kRowBytes));
   };
   auto issue_rj = [&](int ct, int buf) {
     if (wave < TC / 64)
@@ -188,7 +181,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   };
   auto issue_tile = [&](int ct, int buf) {
 #pragma unroll
-    for (int jj = 0; jj < LOADS / NW; ++jj) issue_rows(ct, buf, jj, std::true_type{});
+    for (int jj = 0; jj < LOADS / NW; ++jj) issue_rows_clamped(ct, buf, jj);
     issue_rj(ct, buf);
   };
   // this workgroup's share of the column tiles: [ct_lo, ct_hi), scanned from ct_hi - 1 downwards
@@ -209,11 +202,11 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   int rowid[RT];                                     // SKIP: the row a lane works for (-1: none); rows can move
   auto row_of = [&](int rt) -> int {
     if constexpr (SKIP) return rowid[rt];
-    else return i0 + rt * tile_rows + lrow;
+    else return tile_row0(rt) + lrow;
   };
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const int rowc = min(i0 + rt * tile_rows + lrow, n - 1);
+    const int rowc = min(tile_row0(rt) + lrow, n - 1);
     rni[rt] = rn[rowc];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
@@ -241,7 +234,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   }
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const int row = i0 + rt * tile_rows + lrow;
+    const int row = tile_row0(rt) + lrow;
     thr[rt] = (row < n && a.beta > 0) ? a.T / rni[rt] : INFINITY;
     sub[rt] = 0.f;
     cnt[rt] = 0;
@@ -288,6 +281,21 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], rf[kk], acc, 0, 0, 0);
+    return acc;
+  };
+  // The last chain on a subtile's fragments, single fragment set: as soon as step kk has been issued its
+  // fragment register is refilled with the next subtile's, which gives every refill about eight MFMA
+  // issue slots before the next subtile's first chain needs it.
+  auto chain_refill = [&](bf16x8 (&kf)[8], const bf16x8 (&rf)[8], const unsigned char* tile, int s_next) -> f32x16 {
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    const int row = s_next * 32 + lrow;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], rf[kk], acc, 0, 0, 0);
+      kf[kk] = *reinterpret_cast<const bf16x8*>(tile + slot_offset(row, kk * 2 + half));
+    }
     return acc;
   };
   // K_i . u = sum of the three pseudo-key columns (accumulator elements 0..2 of lanes with half == 0)
@@ -373,7 +381,10 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   // accumulator elements are in ascending key order, so the last hit met wins; the two lanes of the row
   // then compare keys.  DIAG: the tile holds the row's own key, which is no partner.
   auto tile_first_hit = [&](const f32x16& acc, const float (&rj)[16], int rt, int c0, auto diag) {
-    const int selfl = row_of(rt) - c0 - 4 * half;            // own key in this lane's numbering, if it is here
+    int selfl = row_of(rt) - c0 - 4 * half;                  // own key in this lane's numbering, if it is here
+    // keep the 16 comparisons with selfl inside this (rare) path: formed ahead of the scan loop they would
+    // occupy 32 scalar registers per row tile for its whole duration
+    if constexpr (decltype(diag)::value) asm volatile("" : "+v"(selfl));
     float best = 0.f;
     int bcol = -1;
 #pragma unroll
@@ -431,7 +442,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   // ---- stream the tiles, most recent first, from iteration it0 on; RTE = row tiles of the wave that take
   // part (RT, or 1 in a narrow row block and after open rows have been gathered).  Returns the iteration
   // to go on with in the one-row-tile form, or nct when the scan is over.
-  int tiles_now = narrow ? NW : NW * RT;               // SKIP: row tiles of the workgroup that may hold open rows
+  int tiles_now = NW * rte;                            // SKIP: row tiles of the workgroup that may hold open rows
   auto scan = [&](auto rte, int it0) __attribute__((always_inline)) -> int {
   constexpr int RTE = decltype(rte)::value;
   for (int it = it0; it < nct; ++it) {
@@ -442,6 +453,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     // branch inside the MFMA/VALU pipeline below.
     const int ctn = gram_next_tile(ct, ct_lo);
     issue_rj(ctn, buf ^ 1);
+    const uint64_t next_src = tile_source(ctn);
+    const uint32_t next_dst = (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds0 + OFF_TILE + (buf ^ 1) * TILE_SPAN + wave_s * 4 * kRowBytes));
     const unsigned char* tile = gram_lds + OFF_TILE + buf * TILE_SPAN;
     const float* rjs = reinterpret_cast<const float*>(gram_lds + OFF_RJ + buf * TC * 4);
 
@@ -462,6 +475,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
     f32x16 acc[2];
     read_k(kf[(NS - 1) % KB], tile, NS - 1);
     read_rj(rj[(NS - 1) % KB], rjs, NS - 1);
+
     // software pipeline over the NS * RTE tiles of this iteration: chain(q) with test(q - 1)
 #pragma unroll
     for (int q2 = 0; q2 <= NS * RTE; ++q2) {
@@ -474,18 +488,17 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
           if (rt == 0 && s > 0) read_k(kf[(s - 1) & 1], tile, s - 1);
           if (RTE > 1 && rt == 1 && s > 0) read_rj(rj[(s - 1) & 1], rjs, s - 1);
           if (RTE == 1 && q2 == 0 && s > 0) read_rj(rj[(s - 1) & 1], rjs, s - 1);   // single row tile: the rest follow the tests
+          acc[q2 & 1] = chain(kf[s % KB], res[rt]);
         } else {
-          // single set: fetch this subtile's fragments now (the previous subtile's chains are issued)
-          // and its r_j one step later (the previous subtile's last test ran in the step before)
-          if (rt == 0 && s < NS - 1) read_k(kf[0], tile, s);
-          if (rt == 1 && s < NS - 1) read_rj(rj[0], rjs, s);
+          // single fragment set: the subtile's last chain refills the fragments behind itself
+          if (rt == RTE - 1 && s > 0) acc[q2 & 1] = chain_refill(kf[0], res[rt], tile, s - 1);
+          else acc[q2 & 1] = chain(kf[0], res[rt]);
         }
-        acc[q2 & 1] = chain(kf[s % KB], res[rt]);
         // the next tile's DMA copies are spread over the steps instead of stalling the wave up front
         constexpr int PER_STEP = (LOADS / NW + NS * RTE - 1) / (NS * RTE);
 #pragma unroll
         for (int d = 0; d < PER_STEP; ++d)
-          if (q2 * PER_STEP + d < LOADS / NW) issue_rows(ctn, buf ^ 1, q2 * PER_STEP + d, std::false_type{});
+          if (q2 * PER_STEP + d < LOADS / NW) issue_rows(next_src, next_dst, q2 * PER_STEP + d);
       }
       if (q2 > 0) {
         const int qp = q2 - 1;
@@ -505,12 +518,16 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
           // subtile sp's test is done: its r_j registers take those of subtile sp - 2
           if (sp >= 2) read_rj(rj[sp & 1], rjs, sp - 2);
         }
+        if constexpr (KB == 1) {
+          // the subtile's last test is done: the single r_j set takes those of the next subtile
+          if (rtp == RTE - 1 && sp > 0) read_rj(rj[0], rjs, sp - 1);
+        }
       }
     }
     } else {
       // a wave without open rows only helps to copy the next tile
 #pragma unroll
-      for (int jj = 0; jj < LOADS / NW; ++jj) issue_rows(ctn, buf ^ 1, jj, std::false_type{});
+      for (int jj = 0; jj < LOADS / NW; ++jj) issue_rows(next_src, next_dst, jj);
     }
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -533,7 +550,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
       }
       if (total == 0) return nct;                        // nothing the remaining columns could change
       const int need = (total + 31) >> 5;
-      if (need * 2 <= tiles_now && it + 1 < nct) {
+      if (need <= NW && need * 2 <= tiles_now && it + 1 < nct) {
         // Gather the open rows: rows that are done are written out now, an open row's state goes to a
         // record (slots in wave, row tile, lane order), and wave w takes records 32 w .. 32 w + 31 as its
         // first row tile, fetching those rows' keys again.
@@ -580,13 +597,20 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   }
   return nct;
   };   // scan
+  // one instantiation of the scan per number of row tiles a wave can hold (the block's rte is uniform)
+  auto scan_rte = [&](int it0) __attribute__((always_inline)) -> int {
+    if constexpr (RT >= 3) {
+      if (rte == 3) return scan(std::integral_constant<int, 3>{}, it0);
+    }
+    if (rte == 2) return scan(std::integral_constant<int, 2>{}, it0);
+    return scan(std::integral_constant<int, 1>{}, it0);
+  };
   if constexpr (SKIP) {
     int it = 0;
-    if (!narrow) it = scan(std::integral_constant<int, RT>{}, 0);
+    if (rte > 1) it = scan_rte(0);
     if (it < nct) scan(std::integral_constant<int, 1>{}, it);
   } else {
-    if (narrow) scan(std::integral_constant<int, 1>{}, 0);
-    else scan(std::integral_constant<int, RT>{}, 0);
+    scan_rte(0);
   }
 
   // ---- closed-form row sums minus the forgiven similarities
@@ -605,15 +629,9 @@ hipError_t launch_shape(GramArgs a, const Plan& pl, hipStream_t stream) {
       hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP, B1>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (configured != hipSuccess) return configured;
-  static_assert(BM == kGramRows && TC == kGramTile, "the plan's split of the similarity pass assumes this shape");
+  static_assert(BM == (SKIP ? kGramRowsSkip : kGramRows) && TC == kGramTile, "the plan's split of the similarity pass assumes this shape");
   const int head_groups = (pl.heads + 7) / 8;
   a.row_blocks = (pl.n + BM - 1) / BM;
-  // Narrow last row blocks live about two thirds as long as the others.  Listing them last makes the
-  // launch end with short workgroups; it also separates them from their head's other workgroups, so
-  // their head's keys are fetched from HBM a second time.  That trade only pays while the launch is
-  // two or three rounds of workgroups long (the last round is then a large share of it and HBM idles).
-  const bool narrow_tail = a.row_blocks > 1 && pl.n - (a.row_blocks - 1) * BM <= NW * 32;
-  a.tail_last = (narrow_tail && (int64_t)pl.heads * a.row_blocks <= 2048) ? 1 : 0;
   const dim3 grid((unsigned)((int64_t)head_groups * 8 * a.row_blocks * a.parts));
   hipLaunchKernelGGL((gram_kernel<NW, RT, TC, WPS, VARIANT, SKIP, B1>), grid, dim3(NW * 64), lds, stream, a);
   return hipGetLastError();
@@ -640,14 +658,15 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.part_cnt = reinterpret_cast<int*>(ws + pl.off_pcnt);
   a.part_pre = reinterpret_cast<float*>(ws + pl.off_ppre);
   if (pl.skip_saturated) {
+    // (two row tiles per wave: the gathering of open rows needs the registers a third one would take)
     if (a.credit != nullptr) return launch_shape<4, 2, 128, 2, kTransposed, true>(a, pl, stream);
     if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit, true>(a, pl, stream);
     return launch_shape<4, 2, 128, 2, kPlain, true>(a, pl, stream);
   }
-  if (a.credit != nullptr) return launch_shape<4, 2, 128, 2, kTransposed, false>(a, pl, stream);
-  if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit, false>(a, pl, stream);       // split only with beta = 1
-  if (pl.beta == 1) return launch_shape<4, 2, 128, 2, kPlain, false, true>(a, pl, stream);
-  return launch_shape<4, 2, 128, 2, kPlain, false>(a, pl, stream);
+  if (a.credit != nullptr) return launch_shape<4, 3, 128, 2, kTransposed, false>(a, pl, stream);
+  if (a.parts > 1) return launch_shape<4, 3, 128, 2, kSplit, false>(a, pl, stream);       // split only with beta = 1
+  if (pl.beta == 1) return launch_shape<4, 3, 128, 2, kPlain, false, true>(a, pl, stream);
+  return launch_shape<4, 3, 128, 2, kPlain, false>(a, pl, stream);
 }
 
 }  // namespace rkv

@@ -28,15 +28,17 @@ RKV_HD int gram_copy_row_clamped(int ct, int tc, int row0, int lane, int n) {
   return r < n - 1 ? r : n - 1;
 }
 
-// Unclamped form: a wave-uniform first row plus the lane's row.  Every real copy made this way lies in a
-// tile that ends at or before n, where both functions are the identity.  The redundant copy of a part's
-// last iteration can name the head's last, partly filled tile; its first row is pulled back so that the
-// four rows stay inside [0, n) (their content does not matter).
-RKV_HD int gram_copy_first_row(int ct, int tc, int row0, int n) {
-  int r = ct * tc + row0;
-  if (r > n - 4) r = n - 4;
+// Unclamped form, used for every copy issued inside the scan: row = tile row + group row + lane row, the first
+// two wave-uniform.  Every copy made this way that is later read lies in a tile that ends at or before n
+// (so n >= tc), where all three functions are the identity.  The copy of a part's last iteration is never
+// read and can name the head's last, partly filled tile: the tile's first row is pulled back so that the
+// tile stays inside [0, n), and a head with fewer than tc candidates reads rows 0 .. min(3, n - 1) only.
+RKV_HD int gram_copy_tile_row0(int ct, int tc, int n) {
+  int r = ct * tc;
+  if (r > n - tc) r = n - tc;
   return r > 0 ? r : 0;
 }
+RKV_HD int gram_copy_group_row(int row_in_tile, int tc, int n) { return n >= tc ? row_in_tile : 0; }
 RKV_HD int gram_copy_lane_row(int lane, int n) {
   const int r = lane >> 4;
   return r < n - 1 ? r : n - 1;

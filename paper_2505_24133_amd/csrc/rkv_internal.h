@@ -12,7 +12,8 @@ namespace rkv {
 constexpr int kHeadDim = 128;        // d
 constexpr int kChunk = 128;          // keys per workgroup in the key pre-pass
 constexpr int kMaxQRows = 64;        // G * alpha rows of observation queries per KV head
-constexpr int kGramRows = 256;       // candidate rows per workgroup of the similarity pass
+constexpr int kGramRows = 384;       // candidate rows per workgroup of the similarity pass (4 waves x 3 row tiles)
+constexpr int kGramRowsSkip = 256;   // the same with RKV_FLAG_SKIP_SATURATED (4 waves x 2 row tiles)
 constexpr int kGramTile = 128;       // keys per streamed column tile of the similarity pass
 constexpr int kGramMaxParts = 16;    // most workgroups that share the column scan of one row block
 constexpr int kGramSplitMaxBlocks = 256;   // the scan is split only when all heads have at most this many row blocks

@@ -31,9 +31,10 @@ int main(int argc, char** argv) {
     for (int ct = hi - 1; ct >= lo; --ct) {
       const int ctn = rkv::gram_next_tile(ct, lo);
       const bool read_later = ctn < ct;             // the last iteration's copy is never read
-      for (int row0 = 0; row0 < TC; row0 += 4)
+      for (int row0 = 0; row0 < TC; row0 += 4)                 // row0 = wave * 4 + jj * 16 over the four waves
         for (int lane = 0; lane < 64; ++lane) {
-          const int r = rkv::gram_copy_first_row(ctn, TC, row0, n) + rkv::gram_copy_lane_row(lane, n);
+          const int r = rkv::gram_copy_tile_row0(ctn, TC, n) + rkv::gram_copy_group_row(row0 & 15, TC, n) +
+                        rkv::gram_copy_group_row(row0 & ~15, TC, n) + rkv::gram_copy_lane_row(lane, n);
           ++copies;
           if (r < 0 || r >= n || (read_later && r != ctn * TC + row0 + (lane >> 4))) {
             std::printf("unclamped copy: n=%d parts=%d part=%d tile=%d next=%d row0=%d lane=%d -> row %d\n", n, parts, part, ct, ctn,
