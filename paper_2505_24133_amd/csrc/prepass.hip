@@ -44,8 +44,11 @@ struct PrepassArgs {
 // statistics need neither LDS nor a workgroup barrier.  AH = 0 is the general path.
 // PAGED: the keys come from a page pool behind a block table and a dense copy of them is written for
 // the similarity pass (a separate instantiation, so that the contiguous case carries none of it).
+// At least three workgroups per compute unit (one wave of each per SIMD): the variants with two query row
+// tiles would otherwise take a few registers too many for a third workgroup, and the kernel lives on the
+// number of key chunks in flight.
 template <bool HAS_Q, int MT, int AH, bool PAGED>
-__global__ __launch_bounds__(kPrepassThreads) void prepass_kernel(PrepassArgs a) {
+__global__ __launch_bounds__(kPrepassThreads, 3) void prepass_kernel(PrepassArgs a) {
   // The logit tile reuses the key tile's LDS once every wave has read its key fragments
   // (MT * 32 rows x 136 floats <= 128 rows x 272 bytes), which lets four workgroups share a CU.
   __shared__ __attribute__((aligned(16))) unsigned char ks[kChunk * kLdsRowBytes];
