@@ -1,0 +1,34 @@
+"""The host-side validation path of the library (argument checks, stride rules, workspace carve-up, the
+split decision of the similarity pass) built with AddressSanitizer and UndefinedBehaviorSanitizer on the
+host code and driven by tests/abi_sanitizer_main.cpp: more than a million size queries over a grid of
+shapes, plus every entry point's refusals.  The device code is the normal build; nothing is launched.
+CPU only."""
+import os
+import shutil
+import subprocess
+
+import pytest
+
+from paper_2505_24133_amd import build as B
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
+def test_host_validation_under_address_and_undefined_behaviour_sanitizers(repo_root, tmp_path):
+    if not all(os.path.exists(os.path.join(B.OBJ, s.replace(".hip", ".o"))) for s in B.SOURCES):
+        B.build()
+    clang = "/opt/rocm/lib/llvm/bin/clang++"
+    api_o, main_o, exe = tmp_path / "api_san.o", tmp_path / "main.o", tmp_path / "abi_san"
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    subprocess.run(["hipcc", *[f for f in B.FLAGS if f != "-O3"], "-O1", "-g", *san, "-c", os.path.join(B.CSRC, "api.hip"),
+                    "-o", str(api_o)], check=True, capture_output=True)
+    subprocess.run([clang, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                    "-I", os.path.join(repo_root, "include"), "-c", os.path.join(repo_root, "tests", "abi_sanitizer_main.cpp"),
+                    "-o", str(main_o)], check=True, capture_output=True)
+    others = [os.path.join(B.OBJ, s.replace(".hip", ".o")) for s in B.SOURCES if s != "api.hip"]
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-o", str(exe),
+                    str(main_o), str(api_o), *others], check=True, capture_output=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=300,
+                       env={**os.environ, "ASAN_OPTIONS": "detect_leaks=0:verify_asan_link_order=0"})
+    assert r.returncode == 0 and r.stdout.strip().startswith("ok "), r.stdout[-2000:] + r.stderr[-4000:]
+    assert int(r.stdout.split()[1]) > 1_000_000
