@@ -255,8 +255,9 @@ def copy_ceiling(torch):
 def other_modes(torch, rkv, w, state, reps=50):
     """The same workload launched in other ways, for context next to the headline figure (ms per step):
     one call per layer back to back on one stream (eager, and replayed from a HIP graph), a high
-    threshold at which only true near-duplicates count as similar, attention-only eviction
-    (lambda = 1, no similarity pass), the exact shortcut of the similarity pass, and in-place compaction."""
+    threshold at which only true near-duplicates count as similar (dense, with the exact shortcut, and with
+    the triangular schedule, which is meant for that case), attention-only eviction (lambda = 1, no
+    similarity pass), the exact shortcut of the similarity pass, and in-place compaction."""
     import dataclasses
     shp, ws = state["shp"], state["ws"]
     qd, kd, vd = state["ins"][0]
@@ -291,7 +292,9 @@ def other_modes(torch, rkv, w, state, reps=50):
     with torch.cuda.graph(graph):
         per_layer()
     res["per_layer_calls_hip_graph_ms"] = timed(graph.replay)
-    for name, change in (("sim_threshold_0.95_ms", {"sim_threshold": 0.95}), ("attention_only_lambda_1_ms", {"lam": 1.0})):
+    for name, change in (("sim_threshold_0.95_ms", {"sim_threshold": 0.95}), ("attention_only_lambda_1_ms", {"lam": 1.0}),
+                         ("sim_threshold_0.95_skip_saturated_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_SKIP_SATURATED}),
+                         ("sim_threshold_0.95_triangular_scan_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_TRIANGULAR_SCAN})):
         alt = dataclasses.replace(shp, **change)
         res[name] = timed(lambda: rkv.rkv_compress(alt, qd, kd, vd, ws=ws, k_out=ko, v_out=vo, kept_idx=idx))
     # the exact shortcut of the similarity pass (a row that has met its beta partners is left alone;

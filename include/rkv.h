@@ -94,6 +94,19 @@ typedef enum {
  * copies the newest then has the lowest redundancy.  Needs 8 more workspace bytes per candidate.
  */
 #define RKV_FLAG_RECENCY_TRANSPOSED 32u
+/*
+ * RKV_FLAG_TRIANGULAR_SCAN: another schedule of the redundancy pass for the default rule with beta = 1, same
+ * result up to the order of a few floating-point operations.  The cosine matrix of Eq. 5 is symmetric, so
+ * only the entries with j < i are formed (by row blocks: about two thirds of the matrix work at the
+ * benchmark sizes, tending to one half for long caches); an entry above T is the most recent partner
+ * candidate of token i among the older tokens and, mirrored, a newer partner of token j, which a 64-bit
+ * atomic maximum per token collects.  A row cannot be left alone after its first partner (its later entries
+ * may be some older token's most recent partner), so every tile that holds an entry above T takes the slow
+ * path: the mode pays only where such entries are rare (high T, little redundancy).  Needs beta == 1 and
+ * neither RKV_FLAG_RECENCY_TRANSPOSED nor RKV_FLAG_SKIP_SATURATED (RKV_ERR_PARAM otherwise) and 16 more
+ * workspace bytes per candidate.
+ */
+#define RKV_FLAG_TRIANGULAR_SCAN 64u
 
 typedef struct {
   int32_t num_problems;      /* P >= 0; an empty batch is valid and enqueues nothing */

@@ -32,7 +32,7 @@ int device_compute_units() {
 static constexpr uint32_t kGqaFlags = RKV_FLAG_GQA_SOFTMAX_THEN_MAX | RKV_FLAG_GQA_SOFTMAX_THEN_MEAN;
 static constexpr uint32_t kKnownFlags =
     RKV_FLAG_SKIP_SATURATED | RKV_FLAG_POOL_AFTER_MEAN | RKV_FLAG_SHARED_SELECTION | kGqaFlags |
-    RKV_FLAG_RECENCY_TRANSPOSED;
+    RKV_FLAG_RECENCY_TRANSPOSED | RKV_FLAG_TRIANGULAR_SCAN;
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -50,6 +50,9 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   if (!(q.lambda >= 0.f && q.lambda <= 1.f) || !(q.sim_threshold >= 0.f && q.sim_threshold <= 1.f) ||
       !(q.eps > 0.f) || !isfinite(q.eps) || q.beta < 0 || q.pool_w < 0 || (q.flags & kGqaFlags) == kGqaFlags)
     return RKV_ERR_PARAM;
+  if ((q.flags & RKV_FLAG_TRIANGULAR_SCAN) != 0 &&
+      (q.beta != 1 || (q.flags & (RKV_FLAG_RECENCY_TRANSPOSED | RKV_FLAG_SKIP_SATURATED)) != 0))
+    return RKV_ERR_PARAM;
   const int64_t pool_rows = q.alpha + ((q.flags & RKV_FLAG_POOL_AFTER_MEAN) ? 1 : 0);
   if (pool_rows * (q.pool_w > 0 ? 2 * (int64_t)q.pool_w : 1) > 16384 || q.pool_w > 1000) return RKV_ERR_UNSUPPORTED;
 
@@ -60,6 +63,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->pool_after_mean = (q.flags & RKV_FLAG_POOL_AFTER_MEAN) != 0;
   pl->shared_selection = (q.flags & RKV_FLAG_SHARED_SELECTION) != 0;
   pl->recency_transposed = (q.flags & RKV_FLAG_RECENCY_TRANSPOSED) != 0;
+  pl->triangular = (q.flags & RKV_FLAG_TRIANGULAR_SCAN) != 0;
   pl->gqa_mode = (q.flags & RKV_FLAG_GQA_SOFTMAX_THEN_MAX) ? 1 : ((q.flags & RKV_FLAG_GQA_SOFTMAX_THEN_MEAN) ? 2 : 0);
   pl->qrows = (pl->gqa_mode == 0) ? q.alpha : G * q.alpha;
   pl->heads = q.num_problems * q.kv_heads;
@@ -127,7 +131,7 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
     const int64_t blocks = (int64_t)pl->heads * ((pl->n + kGramRows - 1) / kGramRows);
     const int nct = (pl->n + kGramTile - 1) / kGramTile;
     pl->gram_parts = 1;
-    if (pl->beta == 1 && !pl->recency_transposed && blocks > 0 && blocks <= kGramSplitMaxBlocks) {
+    if (pl->beta == 1 && !pl->recency_transposed && !pl->triangular && blocks > 0 && blocks <= kGramSplitMaxBlocks) {
       parts_reserved = std::min(nct, kGramMaxParts);
       const int64_t slots = 2 * (int64_t)device_compute_units();
       if (blocks <= slots / 2)
@@ -146,10 +150,11 @@ rkv_status make_plan(const rkv_params* prm, Plan* pl) {
   pl->off_imp = take(heads * np * 4);
   pl->off_red = take(heads * np * 4);
   pl->off_z = take(heads * np * 4);
-  pl->off_credit = take(pl->recency_transposed ? heads * np * 8 : 0);
+  pl->off_credit = take(pl->recency_transposed || pl->triangular ? heads * np * 8 : 0);
   const size_t parts = (size_t)parts_reserved;
-  pl->off_pcnt = take(parts > 1 ? heads * parts * np * 4 : 0);
-  pl->off_ppre = take(parts > 1 ? heads * parts * np * 4 : 0);
+  const bool reports = parts > 1 || pl->triangular;          // per-row reports merged by the finalize kernel
+  pl->off_pcnt = take(reports ? heads * parts * np * 4 : 0);
+  pl->off_ppre = take(reports ? heads * parts * np * 4 : 0);
   pl->off_kdense = take(pl->paged ? heads * np * kHeadDim * 2 : 0);
   pl->off_idx = take(heads * (size_t)pl->budget * 4);
   pl->total = off;

@@ -46,6 +46,7 @@ struct FinArgs {
   const int* part_cnt;   // [heads][parts][n_pad]
   const float* part_pre; // [heads][parts][n_pad]
   int parts;
+  const unsigned long long* newer;   // [heads][n_pad] or nullptr: triangular scan, most recent newer partner per token
   int pool_after_mean;
   int rows, G, group_mode;   // rows = logit rows per head: alpha, or G * alpha when group_mode != 0
   float lambda;
@@ -194,6 +195,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   const bool pool_after_mean = PLAIN ? false : a.pool_after_mean != 0;
   const int sim_parts = PLAIN ? 1 : a.parts;
   const unsigned long long* credit = PLAIN ? nullptr : a.credit;
+  const unsigned long long* newer = PLAIN ? nullptr : a.newer;
   const float* lg = a.logit + (int64_t)head * qrows * a.n_pad;
   float* sb = a.sbar + (int64_t)head * a.n_pad;
 
@@ -233,6 +235,20 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
           }
         }
         sb[i] -= a.rnorm[(int64_t)head * a.n_pad + i] * forgiven * inv_n;
+      }
+    }
+    if (newer != nullptr) {
+      // triangular scan: a token's most recent partner is the newest token that reported it (the word holds
+      // row << 32 | similarity), else the older one its own row met first
+      const unsigned long long* nw = newer + (int64_t)head * a.n_pad;
+      const float inv_n = 1.0f / (float)n;
+      for (int i = t; i < n; i += kFinThreads) {
+        const unsigned long long w = nw[i];
+        float forgiven = 0.f;
+        if (w != 0ull) forgiven = __uint_as_float((uint32_t)w);
+        else if (a.part_cnt[(int64_t)head * a.n_pad + i] > 0)
+          forgiven = a.rnorm[(int64_t)head * a.n_pad + i] * a.part_pre[(int64_t)head * a.n_pad + i];
+        sb[i] -= forgiven * inv_n;
       }
     }
     if (credit != nullptr) {
@@ -482,6 +498,7 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   a.stats = reinterpret_cast<const float*>(ws + pl.off_stats);
   a.sbar = reinterpret_cast<float*>(ws + pl.off_sbar);
   a.credit = pl.recency_transposed ? reinterpret_cast<const unsigned long long*>(ws + pl.off_credit) : nullptr;
+  a.newer = pl.triangular ? reinterpret_cast<const unsigned long long*>(ws + pl.off_credit) : nullptr;
   a.imp_in = imp_in; a.red_in = red_in;
   a.imp_out = imp_out; a.red_out = red_out; a.sbar_out = sbar_out; a.score_out = score_out;
   a.kept = kept_idx;
@@ -515,7 +532,7 @@ hipError_t launch_finalize(const Plan& pl, int mode, char* ws,
   // the instantiations without the variants' branches serve the default readings with W a positive
   // multiple of two (other shapes and flags take the general one; only the fused modes are doubled)
   const bool plain_imp = pl.gqa_mode == 0 && !pl.pool_after_mean && pl.W > 0 && (pl.W & 1) == 0;
-  const bool plain_red = pl.gram_parts == 1 && !pl.recency_transposed;
+  const bool plain_red = pl.gram_parts == 1 && !pl.recency_transposed && !pl.triangular;
   const bool paper_window = pl.alpha == 8 && pl.W == 4;
   if (plain_imp && plain_red && mode == (kModeImportance | kModeRedundancy | kModeSelect)) {
     if (paper_window) return launch_plain<kModeImportance | kModeRedundancy | kModeSelect, 2>(a, pl.heads, lds, stream);

@@ -72,7 +72,9 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t l
 //   kPlain       one workgroup scans all columns of its rows and writes the mean similarity
 //   kSplit       the scan is shared by several workgroups, each reports what it found (beta = 1)
 //   kTransposed  forgiven similarities are charged to the recent partner's counter
-enum GramVariant : int { kPlain = 0, kSplit = 1, kTransposed = 2 };
+//   kTriangular  only entries with key < row are looked at (the matrix is symmetric): a row block scans the
+//                column tiles up to its own; an entry above T is reported to both of its tokens (beta = 1)
+enum GramVariant : int { kPlain = 0, kSplit = 1, kTransposed = 2, kTriangular = 3 };
 // SKIP adds the exact shortcut: a row that has met beta partners can gain nothing from the columns still
 // to come, so a wave whose rows are all done stops forming tiles, a workgroup whose rows are all done
 // leaves the scan, and when the rows still open fit into half as many row tiles as are in use they are
@@ -188,8 +190,12 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
   const int nct_all = (a.beta > 0) ? (n + TC - 1) / TC : 0;
   int ct_lo, ct_hi;
   gram_part_range(part, parts, nct_all, &ct_lo, &ct_hi);
+  if constexpr (VARIANT == kTriangular) {
+    // nothing newer than the block's last row is needed: its mirror entry belongs to another row
+    ct_hi = min(ct_hi, (min(rb * BM + BM, n) - 1) / TC + 1);
+  }
   const int nct = ct_hi - ct_lo;
-  const bool split = parts > 1;
+  const bool split = parts > 1 || VARIANT == kTriangular;   // rows report to the finalize kernel instead of closing their sum
   const bool closing = part == parts - 1;           // the part that also writes the closed-form row sums
   if (nct > 0) issue_tile(ct_hi - 1, 0);
 
@@ -377,6 +383,50 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
       if (cnt[rt] >= a.beta) thr[rt] = INFINITY;
     }
   };
+  // Triangular scan (beta = 1): every entry above T with key < row is (a) a candidate for the row's most
+  // recent OLDER partner, of which the first one met in the descending scan is kept, and (b) a NEWER partner
+  // of the key's token: the largest row index wins a 64-bit atomic maximum (row << 32 | similarity bits; a
+  // similarity above T >= 0 is a positive float, whose bit pattern orders like its value).  The row's
+  // threshold stays as it is: later entries may still matter to their key.
+  auto tile_triangular = [&](const f32x16& acc, const float (&rj)[16], int rt, int c0) {
+    const int row = row_of(rt);
+    const float r_i = rni[rt];
+    int keyl = row - c0 - 4 * half;                          // keys of this lane's numbering below keyl are older than the row
+    asm volatile("" : "+v"(keyl));
+    float tv[16];
+    uint32_t mine0 = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      tv[i] = acc[i] * rj[i];
+      if (tv[i] > thr[rt] && 8 * (i >> 2) + (i & 3) < keyl) mine0 |= 1u << (8 * (i >> 2) + (i & 3));
+    }
+    if (mine0 != 0u) {
+      unsigned long long* up = a.credit + (int64_t)head * a.n_pad + c0 + 4 * half;
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if ((mine0 >> (8 * (i >> 2) + (i & 3))) & 1u)
+          atomicMax(up + 8 * (i >> 2) + (i & 3),
+                    ((unsigned long long)(uint32_t)row << 32) | (unsigned long long)__float_as_uint(tv[i] * r_i));
+    }
+    const uint32_t mine = mine0 << (4 * half);
+    const auto both = __builtin_amdgcn_permlane32_swap(mine, mine, false, false);
+    const uint32_t all = both[0] | both[1];
+    if (all != 0u && cnt[rt] == 0) {
+      const uint32_t top = 1u << (31 - __clz(all));
+      float s = 0.f;
+      if (mine & top) {
+        const int pos = (31 - __clz(all)) - 4 * half;          // bit position = 8*(i/4) + i%4
+        const bool b0 = pos & 1, b1 = pos & 2, b2 = pos & 8, b3 = pos & 16;
+        const float l0 = b0 ? tv[1] : tv[0], l1 = b0 ? tv[3] : tv[2], l2 = b0 ? tv[5] : tv[4], l3 = b0 ? tv[7] : tv[6];
+        const float l4 = b0 ? tv[9] : tv[8], l5 = b0 ? tv[11] : tv[10], l6 = b0 ? tv[13] : tv[12], l7 = b0 ? tv[15] : tv[14];
+        const float m0 = b1 ? l1 : l0, m1 = b1 ? l3 : l2, m2 = b1 ? l5 : l4, m3 = b1 ? l7 : l6;
+        const float n0 = b2 ? m1 : m0, n1 = b2 ? m3 : m2;
+        s = b3 ? n1 : n0;
+      }
+      sub[rt] = pair_sum32(s);                               // the other lane of the row adds 0
+      cnt[rt] = 1;
+    }
+  };
   // beta = 1 (B1): the row's most recent hit in this tile is all that is wanted.  Within a lane the
   // accumulator elements are in ascending key order, so the last hit met wins; the two lanes of the row
   // then compare keys.  DIAG: the tile holds the row's own key, which is no partner.
@@ -506,7 +556,9 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
         const float m = tile_max(acc[qp & 1], rj[sp % KB]);
         if (q2 < NS * RTE) interleave();
         if (__any(m > thr[rtp])) {
-          if constexpr (B1) {
+          if constexpr (VARIANT == kTriangular) {
+            tile_triangular(acc[qp & 1], rj[sp % KB], rtp, ct * TC + sp * 32);
+          } else if constexpr (B1) {
             const int c0 = ct * TC + sp * 32;
             if (c0 == i0 + rtp * 32) tile_first_hit(acc[qp & 1], rj[sp % KB], rtp, c0, std::true_type{});
             else tile_first_hit(acc[qp & 1], rj[sp % KB], rtp, c0, std::false_type{});
@@ -645,7 +697,7 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
   a.rnorm = reinterpret_cast<const float*>(ws + pl.off_rnorm);
   a.upart = reinterpret_cast<const float*>(ws + pl.off_upart);
   a.sbar = reinterpret_cast<float*>(ws + pl.off_sbar);
-  a.credit = pl.recency_transposed ? reinterpret_cast<unsigned long long*>(ws + pl.off_credit) : nullptr;
+  a.credit = (pl.recency_transposed || pl.triangular) ? reinterpret_cast<unsigned long long*>(ws + pl.off_credit) : nullptr;
   a.H = pl.H; a.heads = pl.heads; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks; a.beta = pl.beta;
   a.ksp = pl.ksp; a.ksh = pl.ksh; a.kst = pl.kst;
   if (pl.paged) {
@@ -663,6 +715,7 @@ hipError_t launch_gram(const Plan& pl, const void* k, char* ws, hipStream_t stre
     if (a.parts > 1) return launch_shape<4, 2, 128, 2, kSplit, true>(a, pl, stream);
     return launch_shape<4, 2, 128, 2, kPlain, true>(a, pl, stream);
   }
+  if (pl.triangular) return launch_shape<4, 3, 128, 2, kTriangular, false>(a, pl, stream);
   if (a.credit != nullptr) return launch_shape<4, 3, 128, 2, kTransposed, false>(a, pl, stream);
   if (a.parts > 1) return launch_shape<4, 3, 128, 2, kSplit, false>(a, pl, stream);       // split only with beta = 1
   if (pl.beta == 1) return launch_shape<4, 3, 128, 2, kPlain, false, true>(a, pl, stream);

@@ -317,7 +317,7 @@ hipError_t launch_prepass(const Plan& pl, const void* q_obs, const void* k, char
   a.k = static_cast<const uint16_t*>(k);
   a.rnorm = reinterpret_cast<float*>(ws + pl.off_rnorm);
   a.upart = reinterpret_cast<float*>(ws + pl.off_upart);
-  a.credit = pl.recency_transposed ? reinterpret_cast<unsigned long long*>(ws + pl.off_credit) : nullptr;
+  a.credit = (pl.recency_transposed || pl.triangular) ? reinterpret_cast<unsigned long long*>(ws + pl.off_credit) : nullptr;
   a.logit = reinterpret_cast<float*>(ws + pl.off_logit);
   a.stats = reinterpret_cast<float*>(ws + pl.off_stats);
   a.H = pl.H; a.G = pl.G; a.alpha = pl.alpha; a.n = pl.n; a.n_pad = pl.n_pad; a.chunks = pl.chunks;

@@ -47,6 +47,7 @@ struct Plan {
   bool pool_after_mean;    // RKV_FLAG_POOL_AFTER_MEAN
   bool shared_selection;   // RKV_FLAG_SHARED_SELECTION
   bool recency_transposed; // RKV_FLAG_RECENCY_TRANSPOSED
+  bool triangular;         // RKV_FLAG_TRIANGULAR_SCAN
   // Similarity pass: the column scan of every row block is split over `gram_parts` workgroups when
   // there are too few row blocks to fill the machine (beta = 1 only: each part reports the first hit of
   // its own column range and finalize keeps the most recent one).
@@ -72,7 +73,9 @@ struct Plan {
   size_t off_red;     // float [heads][n_pad]           redundancy (fused path)
   size_t off_z;       // float [heads][n_pad]           per-head scores Z (shared selection)
   size_t off_credit;  // u64   [heads][n_pad]           forgiven similarity charged to the recent partner, in
-                      //                                units of 2^-40 (RKV_FLAG_RECENCY_TRANSPOSED only)
+                      //                                units of 2^-40 (RKV_FLAG_RECENCY_TRANSPOSED), or the most
+                      //                                recent newer partner, row << 32 | similarity bits
+                      //                                (RKV_FLAG_TRIANGULAR_SCAN)
   size_t off_pcnt;    // int   [heads][gram_parts][n_pad]    hits found per row and column part (gram_parts > 1)
   size_t off_ppre;    // float [heads][gram_parts][n_pad]    sum of those hits
   size_t off_idx;     // int   [heads][budget]          kept indices when the caller passes none

@@ -30,6 +30,7 @@ RKV_FLAG_SHARED_SELECTION = 4
 RKV_FLAG_GQA_SOFTMAX_THEN_MAX = 8
 RKV_FLAG_GQA_SOFTMAX_THEN_MEAN = 16
 RKV_FLAG_RECENCY_TRANSPOSED = 32
+RKV_FLAG_TRIANGULAR_SCAN = 64
 RKV_STATIC_SCRATCH_BYTES = 32 << 20
 
 

@@ -75,7 +75,13 @@ def test_workspace_size_and_validation(lib):
     assert ws_status(lib, shape(budget=8))[0] == rkv.RKV_ERR_SHAPE
     assert ws_status(lib, shape(n_tokens=8))[0] == rkv.RKV_ERR_SHAPE
     assert ws_status(lib, shape(head_dim=64))[0] == rkv.RKV_ERR_UNSUPPORTED
-    assert ws_status(lib, shape(flags=64))[0] == rkv.RKV_ERR_UNSUPPORTED           # unknown flag bit
+    assert ws_status(lib, shape(flags=128))[0] == rkv.RKV_ERR_UNSUPPORTED          # unknown flag bit
+    # the triangular schedule of the similarity pass: beta = 1 only, not with the other direction of the rule or the shortcut
+    assert ws_status(lib, shape(flags=64))[0] == rkv.RKV_OK
+    assert ws_status(lib, shape(flags=64, num_problems=64))[1] > ws_status(lib, shape(num_problems=64))[1]     # 16 more bytes per candidate
+    assert ws_status(lib, shape(flags=64, beta=2))[0] == rkv.RKV_ERR_PARAM
+    assert ws_status(lib, shape(flags=64 | 32))[0] == rkv.RKV_ERR_PARAM
+    assert ws_status(lib, shape(flags=64 | 1))[0] == rkv.RKV_ERR_PARAM
     assert ws_status(lib, shape(flags=15))[0] == rkv.RKV_OK
     assert ws_status(lib, shape(flags=8 | 16))[0] == rkv.RKV_ERR_PARAM             # two ways of merging the group at once
     # merging after the softmax keeps G * alpha logit rows per head: a larger workspace

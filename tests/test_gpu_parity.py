@@ -316,6 +316,42 @@ def test_pseudo_code_variants(case, variant):
     run_fused(w, q, k, v, [(p, h) for p in range(2) for h in range(H)], f"{variant}{N}", check_parts=True, flags=flags)
 
 
+TRIANGULAR_SHAPES = [c for c in ADVERSARIAL if c[6] == 1] + [
+    # N, budget, kv_heads, G, alpha, W, beta, T, lam
+    (392, 300, 2, 4, 8, 4, 1, 0.5, 0.1),      # exactly one row block (384 candidates)
+    (393, 300, 2, 4, 8, 4, 1, 0.9, 0.1),      # one candidate in a second row block
+    (1300, 1100, 3, 4, 8, 4, 1, 0.0, 0.1),    # T = 0: every positive similarity counts
+    (1300, 1100, 1, 4, 8, 4, 1, 1.0, 0.1),    # T = 1: nothing ever counts
+]
+
+
+@pytest.mark.parametrize("case", TRIANGULAR_SHAPES, ids=lambda c: f"N{c[0]}_b{c[1]}_G{c[3]}_a{c[4]}_W{c[5]}_T{c[7]}")
+def test_triangular_scan_gives_the_default_rule(case):
+    """RKV_FLAG_TRIANGULAR_SCAN is another schedule of the similarity pass (entries with j < i only, each
+    reported to both of its tokens), not another rule: its results are compared with the same oracle."""
+    N, budget, H, G, alpha, W, beta, T, lam = case
+    w = synth.Workload("tri", 2, H, H * G, N, budget, alpha=alpha, pool_w=W, beta=beta, sim_threshold=T,
+                       lam=lam, seed=300 + N, recipe="rowcopy", redundancy=0.35, copy_noise=0.15)
+    q, k, v = synth.make_batch(w)
+    run_fused(w, q, k, v, [(p, h) for p in range(2) for h in range(H)], f"tri{N}", check_parts=True,
+              flags=rkv.RKV_FLAG_TRIANGULAR_SCAN)
+
+
+def test_triangular_scan_on_benchmark_shapes():
+    """cfg2 at T = 0.95 (entries above T are rare: the case the schedule is for) and at T = 0.5, cfg3's long
+    heads, all heads of the problems drawn against the oracle; and the scores next to the default schedule's."""
+    for w in (synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=4, sim_threshold=0.95),
+              synth.scaled(synth.CONFIGS["cfg2_llama8b_b1024"], num_problems=2),
+              synth.scaled(synth.CONFIGS["cfg3_llama8b_b4096"], num_problems=1, sim_threshold=0.9)):
+        q, k, v = synth.make_batch(w)
+        heads = [(p, h) for p in range(w.num_problems) for h in range(w.kv_heads)]
+        idx, score, ko, vo = run_fused(w, q, k, v, heads, f"tri_{w.name}_T{w.sim_threshold}", flags=rkv.RKV_FLAG_TRIANGULAR_SCAN)
+        st, ko2, vo2, idx2, score2 = rkv.rkv_compress(shape_of(w, w.num_problems), dev_bf16(q), dev_bf16(k), dev_bf16(v), want_score=True)
+        torch.cuda.synchronize()
+        a, b = score.cpu().numpy().astype(np.float64), score2.cpu().numpy().astype(np.float64)
+        assert np.max(np.abs(a - b) / (np.abs(b) + 1e-12)) < 1e-4       # same rule; the last operations differ in order
+
+
 def test_pseudo_code_variants_cfg2_full_size():
     """Both variants at the benchmark's launch shape; four problems (32 heads) against the oracle."""
     w = synth.CONFIGS["cfg2_llama8b_b1024"]
