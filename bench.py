@@ -292,6 +292,22 @@ def other_modes(torch, rkv, w, state, reps=50):
     with torch.cuda.graph(graph):
         per_layer()
     res["per_layer_calls_hip_graph_ms"] = timed(graph.replay)
+    # the same per-layer calls dealt to four streams (default priority, a workspace each): kernels of
+    # different layers then share the machine, which one call per layer leaves mostly idle
+    lanes = [torch.cuda.Stream() for _ in range(4)]
+    lane_ws = [rkv.make_workspace(one) for _ in lanes]
+
+    def per_layer_streams():
+        main = torch.cuda.current_stream()
+        for s_ in lanes:
+            s_.wait_stream(main)
+        for l in layers:
+            with torch.cuda.stream(lanes[l % 4]):
+                rkv.rkv_compress(one, qd[l:l + 1], kd[l:l + 1], vd[l:l + 1], ws=lane_ws[l % 4], k_out=ko[l:l + 1],
+                                 v_out=vo[l:l + 1], kept_idx=idx[l:l + 1])
+        for s_ in lanes:
+            main.wait_stream(s_)
+    res["per_layer_calls_4_streams_ms"] = timed(per_layer_streams)
     for name, change in (("sim_threshold_0.95_ms", {"sim_threshold": 0.95}), ("attention_only_lambda_1_ms", {"lam": 1.0}),
                          ("sim_threshold_0.95_skip_saturated_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_SKIP_SATURATED}),
                          ("sim_threshold_0.95_triangular_scan_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_TRIANGULAR_SCAN})):

@@ -223,8 +223,7 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
   if constexpr ((MODE & kModeRedundancy) != 0) {
     if (sim_parts > 1) {
       // beta = 1 (the only case that is split): the most recent column part that found a hit supplies
-      // the forgiven similarity
-      const float inv_n = 1.0f / (float)n;
+      // the forgiven similarity; the slot holds the closed form until now
       for (int i = t; i < n; i += kFinThreads) {
         float forgiven = 0.f;
         for (int p = sim_parts - 1; p >= 0; --p) {
@@ -234,21 +233,19 @@ __global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
             break;
           }
         }
-        sb[i] -= a.rnorm[(int64_t)head * a.n_pad + i] * forgiven * inv_n;
+        sb[i] = mean_sim_finish(sb[i], a.rnorm[(int64_t)head * a.n_pad + i], forgiven, n);
       }
     }
     if (newer != nullptr) {
       // triangular scan: a token's most recent partner is the newest token that reported it (the word holds
       // row << 32 | similarity), else the older one its own row met first
       const unsigned long long* nw = newer + (int64_t)head * a.n_pad;
-      const float inv_n = 1.0f / (float)n;
       for (int i = t; i < n; i += kFinThreads) {
         const unsigned long long w = nw[i];
-        float forgiven = 0.f;
-        if (w != 0ull) forgiven = __uint_as_float((uint32_t)w);
-        else if (a.part_cnt[(int64_t)head * a.n_pad + i] > 0)
-          forgiven = a.rnorm[(int64_t)head * a.n_pad + i] * a.part_pre[(int64_t)head * a.n_pad + i];
-        sb[i] -= forgiven * inv_n;
+        const float r = a.rnorm[(int64_t)head * a.n_pad + i];
+        // the reported similarity is complete (both norms in it): finished as 1 * similarity
+        if (w != 0ull) sb[i] = mean_sim_finish(sb[i], 1.0f, __uint_as_float((uint32_t)w), n);
+        else sb[i] = mean_sim_finish(sb[i], r, a.part_cnt[(int64_t)head * a.n_pad + i] > 0 ? a.part_pre[(int64_t)head * a.n_pad + i] : 0.f, n);
       }
     }
     if (credit != nullptr) {

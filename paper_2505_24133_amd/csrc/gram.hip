@@ -475,16 +475,15 @@ __global__ __launch_bounds__(NW * 64, WPS) void gram_kernel(GramArgs a) {
       float r;
       if constexpr (SKIP) r = rn[row];                   // rows may have moved between lanes
       else r = rni[rt];                                  // still in the register it was loaded into
-      const float self = 1.0f - a.eps * r;               // r_i |K_i| = 1 - eps r_i
+      const float closed = mean_sim_closed(r, rowdot[rt], a.eps);
       if (!split) {
-        const float total = r * rowdot[rt] - self * self - r * sub[rt];
-        a.sbar[(int64_t)head * a.n_pad + row] = total / (float)n;
+        a.sbar[(int64_t)head * a.n_pad + row] = mean_sim_finish(closed, r, sub[rt], n);
       } else {
-        // finalize subtracts the forgiven similarity once every part has reported its hit (beta = 1:
-        // the most recent part that found one supplies it)
+        // the finalize kernel finishes the mean once every part has reported its hit (beta = 1: the most
+        // recent part that found one supplies it); until then the slot holds the closed form
         a.part_cnt[((int64_t)head * parts + part) * a.n_pad + row] = cnt[rt];
         a.part_pre[((int64_t)head * parts + part) * a.n_pad + row] = sub[rt];
-        if (closing) a.sbar[(int64_t)head * a.n_pad + row] = (r * rowdot[rt] - self * self) / (float)n;
+        if (closing) a.sbar[(int64_t)head * a.n_pad + row] = closed;
       }
     }
   };

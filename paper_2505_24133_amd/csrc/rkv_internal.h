@@ -123,6 +123,19 @@ hipError_t launch_append(const Plan& pl, void* k_cache, void* v_cache, void* q_r
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
+// Mean similarity of a token (Eq. 6) from its closed-form parts, in ONE fixed sequence of rounded operations
+// wherever it is finished (by the similarity kernel itself, or by the finalize kernel when the token's
+// column scan was shared by several workgroups), so that the result does not depend on the schedule:
+//   closed = r (K_i . u) - (r |K_i|)^2          [row sum of the cosine matrix, diagonal taken off]
+//   mean   = (closed - r * forgiven) / n        [forgiven: sum over the forgiven partners of (K_i . K_j) r_j]
+__device__ __forceinline__ float mean_sim_closed(float r, float rowdot, float eps) {
+  const float self = __fmaf_rn(-eps, r, 1.0f);             // r |K_i| = 1 - eps r
+  return __fmaf_rn(r, rowdot, -__fmul_rn(self, self));
+}
+__device__ __forceinline__ float mean_sim_finish(float closed, float r, float forgiven, int n) {
+  return __fdiv_rn(__fmaf_rn(-r, forgiven, closed), (float)n);
+}
+
 // Reduction steps between lane l and lane l ^ 16 (or l ^ 32) with the gfx950 row-swap instructions:
 // after the swap both lanes of a pair hold (value of the lower lane, value of the upper lane), so
 // the two get bit-identical results without a trip through LDS.

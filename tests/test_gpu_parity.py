@@ -447,6 +447,26 @@ def test_bit_identical_on_repeat_and_on_another_stream():
             assert torch.equal(x, y)
 
 
+def test_results_do_not_depend_on_how_the_similarity_pass_is_scheduled():
+    """With few heads the column scan of every row block is shared by several workgroups and the finalize
+    kernel finishes the mean similarity; with many heads one workgroup does it all.  Both finish it with
+    the same sequence of rounded operations, so a problem gives the same bits alone and inside a batch."""
+    w = synth.CONFIGS["cfg2_llama8b_b1024"]
+    q, k, v = synth.make_batch(w, workers=Hp.oracle_workers())
+    qd, kd, vd = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    say("full batch (one workgroup per row block) vs two problems alone (split column scan)")
+    full = shape_of(w, w.num_problems)
+    red_a, msim_a = rkv.rkv_score_redundancy(full, kd, want_mean_sim=True)
+    out_a = rkv.rkv_compress(full, qd, kd, vd, want_score=True)
+    few = shape_of(w, 2)
+    red_b, msim_b = rkv.rkv_score_redundancy(few, kd[5:7].contiguous(), want_mean_sim=True)
+    out_b = rkv.rkv_compress(few, qd[5:7].contiguous(), kd[5:7].contiguous(), vd[5:7].contiguous(), want_score=True)
+    torch.cuda.synchronize()
+    assert torch.equal(msim_a[5:7], msim_b) and torch.equal(red_a[5:7], red_b)
+    for x, y in zip(out_a[1:], out_b[1:]):
+        assert torch.equal(x[5:7], y)
+
+
 def test_strided_cache_views():
     """K/V given as views of a larger [P, H, N_alloc, d] allocation (static cache with spare rows)."""
     w = synth.scaled(synth.CONFIGS["cfg1_tiny"], num_problems=2, kv_heads=2)
