@@ -173,8 +173,11 @@ constexpr int kModeZ = kModeSelect | kModeScore;     // modes that form the join
 
 // PLAIN != 0: the default readings with a window that is a multiple of four wide and an unsplit
 // similarity pass; the variants' branches are then compiled out of the instantiation.
+// The instantiations for the default readings with the paper's window sizes keep to 64 vector registers, so that two workgroups (eight
+// waves per SIMD) share a compute unit when there are many heads; left to itself the register allocator
+// takes more for them as soon as unrelated code of the general instantiations changes.
 template <int MODE, int PLAIN>
-__global__ __launch_bounds__(kFinThreads) void finalize_kernel(FinArgs a) {
+__global__ __launch_bounds__(kFinThreads, PLAIN == 2 ? 8 : 4) void finalize_kernel(FinArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t keys[];   // n_pad order-preserving keys (select mode) / pooling stage
   __shared__ float red[kFinWaves];
   __shared__ uint32_t scan_buf[kFinWaves];
