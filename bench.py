@@ -308,11 +308,18 @@ def other_modes(torch, rkv, w, state, reps=50):
         for s_ in lanes:
             main.wait_stream(s_)
     res["per_layer_calls_4_streams_ms"] = timed(per_layer_streams)
+    # and that fork-join pattern replayed from a HIP graph (no host time per call)
+    torch.cuda.synchronize()
+    graph4 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph4):
+        per_layer_streams()
+    res["per_layer_calls_4_streams_hip_graph_ms"] = timed(graph4.replay)
     for name, change in (("sim_threshold_0.95_ms", {"sim_threshold": 0.95}), ("attention_only_lambda_1_ms", {"lam": 1.0}),
                          ("sim_threshold_0.95_skip_saturated_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_SKIP_SATURATED}),
                          ("sim_threshold_0.95_triangular_scan_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_TRIANGULAR_SCAN})):
         alt = dataclasses.replace(shp, **change)
-        res[name] = timed(lambda: rkv.rkv_compress(alt, qd, kd, vd, ws=ws, k_out=ko, v_out=vo, kept_idx=idx))
+        alt_ws = rkv.make_workspace(alt)             # some flags need more scratch than the default call
+        res[name] = timed(lambda: rkv.rkv_compress(alt, qd, kd, vd, ws=alt_ws, k_out=ko, v_out=vo, kept_idx=idx))
     # the exact shortcut of the similarity pass (a row that has met its beta partners is left alone;
     # same results, data-dependent time: with these keys nearly every row is done after one column tile)
     alt = dataclasses.replace(shp, flags=shp.flags | rkv.RKV_FLAG_SKIP_SATURATED)
