@@ -252,6 +252,25 @@ def copy_ceiling(torch):
     return 10 * 2 * (256 << 20) / (t0.elapsed_time(t1) * 1e-3) / 1e9
 
 
+def mfma_sustained(torch, rkv, keys):
+    """What the matrix pipe sustains on the similarity pass's MFMA instruction alone (TFLOP/s): launches of
+    about a millisecond that issue nothing else, on fragments of the workload's keys, back to back for a
+    quarter of a second; the second half is timed.  The published peak assumes the top clock; this is the
+    rate at the clock the chip settles at on such data."""
+    ops = keys.reshape(-1)[: rkv.RKV_PROBE_OPERAND_BYTES // 2].contiguous()
+    sink = torch.empty(rkv.RKV_PROBE_SINK_BYTES // 4, dtype=torch.float32, device="cuda")
+    chains, launches = 6000, 120
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    flops = 0
+    for i in range(2 * launches):
+        if i == launches:
+            t0.record()
+        flops = rkv.rkv_probe_mfma(ops, sink, chains)
+    t1.record()
+    torch.cuda.synchronize()
+    return launches * flops / (t0.elapsed_time(t1) * 1e-3) / 1e12
+
+
 def other_modes(torch, rkv, w, state, reps=50):
     """The same workload launched in other ways, for context next to the headline figure (ms per step):
     one call per layer back to back on one stream (eager, and replayed from a HIP graph), a high
@@ -441,8 +460,12 @@ def main() -> int:
             ko, vo, idx = state["outs"][0]
             rkv.rkv_compress(shp, qd, kd, vd, ws=ws, k_out=ko, v_out=vo, kept_idx=idx)
     out["device"] = {"name": torch.cuda.get_device_name(0), "clocks_under_load": sclk_under_load(torch, burst),
-                     "device_copy_GB/s": copy_ceiling(torch), "published_peaks": {"bf16_mfma_TFLOP/s": 2500.0, "hbm_GB/s": 8000.0}}
+                     "device_copy_GB/s": copy_ceiling(torch),
+                     "mfma_sustained_TFLOP/s": mfma_sustained(torch, rkv, state["ins"][0][1]), "published_peaks": {"bf16_mfma_TFLOP/s": 2500.0, "hbm_GB/s": 8000.0}}
 
+    if out["roofline"]["bound"] == "mfma":
+        # the similarity kernel's rate against what the matrix pipe sustains (the roofline entry keeps the published peak)
+        out["device"]["gram_over_mfma_sustained"] = round(out["roofline"]["achieved"] / out["device"]["mfma_sustained_TFLOP/s"], 4)
     if plain and not args.no_other_modes:
         out["other_modes"] = other_modes(torch, rkv, w, state)
     del state
@@ -470,6 +493,8 @@ def main() -> int:
             out["workloads"][name]["steps"] = k_steps
             t_bytes, t_src = gram_traffic(name)
             out["workloads"][name]["gram_traffic"] = t_bytes
+            if o_stages["gram"].get("TFLOP/s"):
+                out["workloads"][name]["gram_over_mfma_sustained"] = round(o_stages["gram"]["TFLOP/s"] / out["device"]["mfma_sustained_TFLOP/s"], 4)
             del o_state, qo, ko_, vo_
             torch.cuda.empty_cache()
             if not args.no_cpu_baseline:

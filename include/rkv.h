@@ -232,6 +232,25 @@ rkv_status rkv_compress_events(const rkv_params* prm, const void* q_obs, const v
                                void* ws, size_t ws_bytes, void* stream, void* const* events);
 
 /*
+ * Measurement aid, not a step of the method: one launch that issues nothing but the bf16 MFMA instruction
+ * the similarity pass (Eq. 5) is built from, in chains of eight on fragments cut from the caller's data, on
+ * every SIMD of the device (two workgroups of four waves per compute unit).  Timed over a few dozen
+ * back-to-back launches it gives the rate the matrix pipe SUSTAINS on such data at the clock the chip
+ * settles at, which is what the similarity kernel's rate is to be read against (the published peak assumes
+ * the top clock).
+ *   operands  device, 16-byte aligned, RKV_PROBE_OPERAND_BYTES of bf16 values (e.g. the start of a key
+ *             cache); read only
+ *   sink      device, RKV_PROBE_SINK_BYTES, overwritten (one float per thread; content of no interest)
+ *   chains    chains of eight MFMAs per wave, 1 .. 2^20
+ *   flops     host pointer or NULL: receives the floating-point operations of the launch
+ * Asynchronous on `stream`.  RKV_ERR_NULL / RKV_ERR_PARAM / RKV_ERR_SHAPE (alignment) before anything is
+ * enqueued, RKV_ERR_WORKSPACE if the device has more compute units than the sink is sized for.
+ */
+#define RKV_PROBE_OPERAND_BYTES (64u << 10)
+#define RKV_PROBE_SINK_BYTES (1u << 20)
+rkv_status rkv_probe_mfma(const void* operands, void* sink, int chains, void* stream, int64_t* flops);
+
+/*
  * Decode-loop bookkeeping (Sec. 3.1; query cache of App. C.1).  The cache holds up to
  * N = n_tokens = B_budget + B_buffer rows per head; a decode step appends one row.
  *

@@ -14,7 +14,7 @@ _BINDING_NAMES = (
     "RKV_FLAG_GQA_SOFTMAX_THEN_MAX", "RKV_FLAG_GQA_SOFTMAX_THEN_MEAN", "RKV_FLAG_POOL_AFTER_MEAN",
     "RKV_FLAG_RECENCY_TRANSPOSED", "RKV_FLAG_SHARED_SELECTION", "RKV_FLAG_TRIANGULAR_SCAN", "RKV_FLAG_SKIP_SATURATED", "RKV_NOT_TRIGGERED",
     "RKV_OK", "RKV_STATIC_SCRATCH_BYTES", "RkvError", "RkvParams", "Shape", "load_library", "make_workspace",
-    "rkv_compact", "rkv_compact_inplace", "rkv_compress", "rkv_compress_inplace", "rkv_compress_static",
+    "rkv_compact", "rkv_compact_inplace", "rkv_compress", "rkv_compress_inplace", "rkv_compress_static", "rkv_probe_mfma",
     "rkv_score_importance", "rkv_score_redundancy", "rkv_select_topk", "rkv_workspace_size", "status_string",
 )
 

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librkv.so")
-SOURCES = ["api.hip", "prepass.hip", "gram.hip", "finalize.hip", "gather.hip", "compact_inplace.hip", "append.hip"]
+SOURCES = ["api.hip", "prepass.hip", "gram.hip", "finalize.hip", "gather.hip", "compact_inplace.hip", "append.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

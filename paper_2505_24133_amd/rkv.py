@@ -32,6 +32,8 @@ RKV_FLAG_GQA_SOFTMAX_THEN_MEAN = 16
 RKV_FLAG_RECENCY_TRANSPOSED = 32
 RKV_FLAG_TRIANGULAR_SCAN = 64
 RKV_STATIC_SCRATCH_BYTES = 32 << 20
+RKV_PROBE_OPERAND_BYTES = 64 << 10
+RKV_PROBE_SINK_BYTES = 1 << 20
 
 
 class RkvParams(ctypes.Structure):
@@ -81,9 +83,10 @@ def load_library() -> ctypes.CDLL:
     lib.rkv_compress_inplace.argtypes = [P, V, V, V, V, V, V, S, V]
     lib.rkv_should_compress.argtypes = [P, ctypes.c_int32]
     lib.rkv_cache_append.argtypes = [P, V, V, V, V, V, V, ctypes.c_int32, ctypes.c_int32, V]
+    lib.rkv_probe_mfma.argtypes = [V, V, ctypes.c_int, V, ctypes.POINTER(ctypes.c_int64)]
     for name in ("rkv_workspace_size", "rkv_score_importance", "rkv_score_redundancy", "rkv_select_topk",
                  "rkv_compact", "rkv_compress", "rkv_compress_events", "rkv_compress_static", "rkv_should_compress", "rkv_cache_append",
-                 "rkv_compact_inplace", "rkv_compress_inplace"):
+                 "rkv_compact_inplace", "rkv_compress_inplace", "rkv_probe_mfma"):
         getattr(lib, name).restype = ctypes.c_int
     lib.rkv_status_string.argtypes = [ctypes.c_int]
     lib.rkv_status_string.restype = ctypes.c_char_p
@@ -387,6 +390,21 @@ def rkv_compress(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Te
     if s < 0:
         raise RkvError(s, "rkv_compress")
     return s, k_out, v_out, kept_idx, score
+
+
+def rkv_probe_mfma(operands: torch.Tensor, sink: torch.Tensor, chains: int) -> int:
+    """Measurement aid: one launch of nothing but the similarity pass's MFMA instruction on fragments of
+    `operands` (bf16, at least RKV_PROBE_OPERAND_BYTES), on the current stream; returns its flop count."""
+    _need_gpu(operands, sink)
+    if operands.dtype != torch.bfloat16 or not operands.is_contiguous() or operands.numel() * 2 < RKV_PROBE_OPERAND_BYTES:
+        raise ValueError("operands: contiguous bf16 tensor of at least RKV_PROBE_OPERAND_BYTES")
+    if not sink.is_contiguous() or sink.numel() * sink.element_size() < RKV_PROBE_SINK_BYTES:
+        raise ValueError("sink: contiguous tensor of at least RKV_PROBE_SINK_BYTES")
+    flops = ctypes.c_int64(0)
+    s = load_library().rkv_probe_mfma(_ptr(operands), _ptr(sink), int(chains), _stream(), ctypes.byref(flops))
+    if s < 0:
+        raise RkvError(s, "rkv_probe_mfma")
+    return flops.value
 
 
 def rkv_compress_static(shape: Shape, q_obs: torch.Tensor, k: torch.Tensor, v: torch.Tensor, k_out: torch.Tensor,

@@ -25,7 +25,7 @@ def declared_symbols(repo_root):
 
 def test_every_declared_symbol_is_exported(lib, repo_root):
     names = declared_symbols(repo_root)
-    assert names == ["rkv_cache_append", "rkv_compact", "rkv_compact_inplace", "rkv_compress", "rkv_compress_events", "rkv_compress_inplace", "rkv_compress_static", "rkv_score_importance", "rkv_score_redundancy",
+    assert names == ["rkv_cache_append", "rkv_compact", "rkv_compact_inplace", "rkv_compress", "rkv_compress_events", "rkv_compress_inplace", "rkv_compress_static", "rkv_probe_mfma", "rkv_score_importance", "rkv_score_redundancy",
                      "rkv_select_topk", "rkv_should_compress", "rkv_status_string", "rkv_workspace_size"]
     for n in names:
         assert hasattr(lib, n), n
@@ -183,6 +183,19 @@ def test_static_scratch_entry_point_validates_on_the_host(lib):
     assert lib.rkv_compress_static(ctypes.byref(p), None, None, None, None, None, None, None, None) == rkv.RKV_OK
     header = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "rkv.h")).read()
     assert "#define RKV_STATIC_SCRATCH_BYTES (32u << 20)" in header and rkv.RKV_STATIC_SCRATCH_BYTES == 32 << 20
+
+
+def test_mfma_probe_validates_on_the_host(lib, repo_root):
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.rkv_probe_mfma(None, fake, 1, None, None) == rkv.RKV_ERR_NULL
+    assert lib.rkv_probe_mfma(fake, None, 1, None, None) == rkv.RKV_ERR_NULL
+    assert lib.rkv_probe_mfma(fake, fake, 0, None, None) == rkv.RKV_ERR_PARAM
+    assert lib.rkv_probe_mfma(fake, fake, (1 << 20) + 1, None, None) == rkv.RKV_ERR_PARAM
+    assert lib.rkv_probe_mfma(ctypes.c_void_p(0x1008), fake, 1, None, None) == rkv.RKV_ERR_SHAPE
+    assert lib.rkv_probe_mfma(fake, ctypes.c_void_p(0x1002), 1, None, None) == rkv.RKV_ERR_SHAPE
+    header = open(os.path.join(repo_root, "include", "rkv.h")).read()
+    assert "#define RKV_PROBE_OPERAND_BYTES (64u << 10)" in header and rkv.RKV_PROBE_OPERAND_BYTES == 64 << 10
+    assert "#define RKV_PROBE_SINK_BYTES (1u << 20)" in header and rkv.RKV_PROBE_SINK_BYTES == 1 << 20
 
 
 def test_status_strings(lib):
