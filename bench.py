@@ -276,7 +276,8 @@ def other_modes(torch, rkv, w, state, reps=50):
     one call per layer back to back on one stream (eager, and replayed from a HIP graph), a high
     threshold at which only true near-duplicates count as similar (dense, with the exact shortcut, and with
     the triangular schedule, which is meant for that case), attention-only eviction (lambda = 1, no
-    similarity pass), the exact shortcut of the similarity pass, and in-place compaction."""
+    similarity pass), the exact shortcut of the similarity pass, in-place compaction, and two sequences in flight
+    on two streams (time per step of either)."""
     import dataclasses
     shp, ws = state["shp"], state["ws"]
     qd, kd, vd = state["ins"][0]
@@ -333,6 +334,20 @@ def other_modes(torch, rkv, w, state, reps=50):
     with torch.cuda.graph(graph4):
         per_layer_streams()
     res["per_layer_calls_4_streams_hip_graph_ms"] = timed(graph4.replay)
+    # two sequences in flight: steps alternate between two streams (own buffers and workspace each), so that one
+    # sequence's memory-bound kernels (pre-pass, gather) share the machine with the other's similarity pass
+    pair = [(qd, kd, vd, ko, vo, idx, ws, torch.cuda.Stream()),
+            (qd.clone(), kd.clone(), vd.clone(), torch.empty_like(ko), torch.empty_like(vo), torch.empty_like(idx),
+             rkv.make_workspace(shp), torch.cuda.Stream())]
+
+    def two_in_flight():
+        for q2, k2, v2, ko2, vo2, idx2, ws2, st in pair:
+            with torch.cuda.stream(st):
+                rkv.rkv_compress(shp, q2, k2, v2, ws=ws2, k_out=ko2, v_out=vo2, kept_idx=idx2)
+    for st in (pair[0][7], pair[1][7]):
+        st.wait_stream(torch.cuda.current_stream())
+    res["two_sequences_two_streams_ms_per_step"] = timed(two_in_flight) / 2
+    del pair
     for name, change in (("sim_threshold_0.95_ms", {"sim_threshold": 0.95}), ("attention_only_lambda_1_ms", {"lam": 1.0}),
                          ("sim_threshold_0.95_skip_saturated_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_SKIP_SATURATED}),
                          ("sim_threshold_0.95_triangular_scan_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_TRIANGULAR_SCAN})):
