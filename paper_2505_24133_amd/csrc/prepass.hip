@@ -65,6 +65,7 @@ __global__ __launch_bounds__(kPrepassThreads, 3) void prepass_kernel(PrepassArgs
   // Persistent workgroups: each walks over (head, chunk) items.  Four workgroups share a compute unit
   // (128 VGPRs, 37 KB of LDS each), so while one waits for its chunk the others compute; holding the
   // next chunk in registers as well cost a workgroup per compute unit and was slower.
+  const uint32_t row_bytes = (uint32_t)a.kst * 2u;
   auto fetch = [&](int hd, int ck, uint4 (&dst)[8]) {
     const int pp = hd / a.H;
     // rows past n repeat row n - 1 (their r is forced to 0 below and their logits are masked)
@@ -80,11 +81,14 @@ __global__ __launch_bounds__(kPrepassThreads, 3) void prepass_kernel(PrepassArgs
       }
     } else {
       const uint16_t* kb = a.k + pp * a.ksp + (hd - pp * a.H) * a.ksh;
+      // The chunk's first row goes into the workgroup-uniform base; what is left per thread is a row inside
+      // the chunk (pulled back to row n - 1 in a head's last chunk) times the row pitch, a 32-bit offset:
+      // rows are at most 65536 bytes apart and a chunk has 128 of them.
+      const unsigned char* cb = reinterpret_cast<const unsigned char*>(kb) + (int64_t)ck * kChunk * row_bytes;
+      const uint32_t last = (uint32_t)(a.n - 1 - ck * kChunk);
 #pragma unroll
-      for (int m = 0; m < 8; ++m) {
-        const int grow = min(ck * kChunk + m * 16 + rbase, a.n - 1);
-        dst[m] = *reinterpret_cast<const uint4*>(kb + (int64_t)grow * a.kst + c16 * 8);
-      }
+      for (int m = 0; m < 8; ++m)
+        dst[m] = *reinterpret_cast<const uint4*>(cb + (min((uint32_t)(m * 16 + rbase), last) * row_bytes + (uint32_t)c16 * 16u));
     }
   };
   uint4 regs[8];
@@ -215,13 +219,14 @@ __global__ __launch_bounds__(kPrepassThreads, 3) void prepass_kernel(PrepassArgs
       float m[AH], mx[AH], e[AH];
 #pragma unroll
       for (int i = 0; i < AH; ++i) {
-        m[i] = acc[0][i];
+        // scaled first (the scale is positive, so the maximum is the same float): products are known to the
+        // compiler as ordinary numbers and the maxima below stay single instructions
+        m[i] = acc[0][i] * a.scale;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
           for (int iq = 0; iq < 16 / AH; ++iq)
-            if (mt * (16 / AH) + iq > 0 && mt * (16 / AH) + iq < a.G) m[i] = fmaxf(m[i], acc[mt][i + iq * AH]);
-        m[i] *= a.scale;
+            if (mt * (16 / AH) + iq > 0 && mt * (16 / AH) + iq < a.G) m[i] = fmaxf(m[i], acc[mt][i + iq * AH] * a.scale);
         if (valid) lgt[(int64_t)(8 * (i >> 2) + 4 * khalf + (i & 3)) * a.n_pad] = m[i];
       }
       // (max, sum exp) over the wave's 32 keys of each row

@@ -147,13 +147,21 @@ __device__ __forceinline__ float pair_sum32(float v) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+// max of two floats as ONE v_max_f32.  fmaxf() on values the compiler cannot see the origin of (lane
+// exchanges, MFMA results) is preceded by an instruction per operand that quiets signalling NaNs; the
+// kernels' inputs hold none, and in the reductions below that tripled the instruction count.
+__device__ __forceinline__ float raw_max(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
 __device__ __forceinline__ float pair_max16(float v) {
   const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return raw_max(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ float pair_max32(float v) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return raw_max(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 // v + (v of the lane selected by the DPP control), within rows of 16 lanes.
@@ -162,10 +170,17 @@ __device__ __forceinline__ float dpp_add(float v) {
   const int x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
   return v + __int_as_float(x);
 }
+// max(v, v of the lane selected by the DPP control) as one instruction; the two wait states a DPP read
+// needs after the vector instruction that wrote its source travel with it.
 template <int CTRL>
 __device__ __forceinline__ float dpp_max(float v) {
-  const int x = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
-  return fmaxf(v, __int_as_float(x));
+  static_assert(CTRL == 0xB1 || CTRL == 0x4E || CTRL == 0x141 || CTRL == 0x140, "the four steps of the row reduction");
+  float r;
+  if constexpr (CTRL == 0xB1) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));
+  else if constexpr (CTRL == 0x4E) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));
+  else if constexpr (CTRL == 0x141) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));
+  else asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_mirror row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));
+  return r;
 }
 // Reductions over the 32 lanes of each half of the wave (every lane of the half ends with the result):
 // four DPP steps inside the rows of 16 lanes, one row swap between the two rows.  The full-wave forms
