@@ -348,6 +348,14 @@ def other_modes(torch, rkv, w, state, reps=50):
         st.wait_stream(torch.cuda.current_stream())
     res["two_sequences_two_streams_ms_per_step"] = timed(two_in_flight) / 2
     del pair
+    # and two sequences batched into one call (twice the problems: the similarity pass's workgroups then fill
+    # whole rounds of the machine)
+    both = dataclasses.replace(shp, num_problems=2 * shp.num_problems)
+    q2, k2, v2 = torch.cat([qd, qd]), torch.cat([kd, kd]), torch.cat([vd, vd])
+    ko2, vo2, idx2 = torch.cat([ko, ko]), torch.cat([vo, vo]), torch.cat([idx, idx])
+    ws2 = rkv.make_workspace(both)
+    res["two_sequences_one_call_ms_per_step"] = timed(lambda: rkv.rkv_compress(both, q2, k2, v2, ws=ws2, k_out=ko2, v_out=vo2, kept_idx=idx2)) / 2
+    del q2, k2, v2, ko2, vo2, idx2, ws2
     for name, change in (("sim_threshold_0.95_ms", {"sim_threshold": 0.95}), ("attention_only_lambda_1_ms", {"lam": 1.0}),
                          ("sim_threshold_0.95_skip_saturated_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_SKIP_SATURATED}),
                          ("sim_threshold_0.95_triangular_scan_ms", {"sim_threshold": 0.95, "flags": rkv.RKV_FLAG_TRIANGULAR_SCAN})):
